@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the shard forward pass on one MI355X.
+
+One *step* is one pass of the whole hot path over one batch of synthetic input on the
+workload the benchmark's metric is quoted on: a Llama2-7B-shaped shard, layers 0-7 of 32,
+fp32 weights, batch 1, a 512-token prefill followed by 128 decode steps.  Weights and all
+inputs are resident in HBM before the timed region.  Prints one JSON line.
+
+  value            decode tokens/s of the shard (tokens generated / time inside shard_decode)
+  decode_gbps      algorithmic bytes of a decode step (weights once + KV read/write + the
+                   boundary activations) / time, and its fraction of 8 TB/s
+  prefill_tflops   algorithmic FLOPs of the prefill (projections + causal half of attention)
+                   / time, and its fraction of the fp32 MFMA peak (157.3 TFLOP/s)
+  roofline         the dominant kernel (the weight-streaming decode projection) from HIP
+                   events around each of its launches, in one extra instrumented step
+  cpu_baseline     the float64 CPU oracle timed on a bounded sample of the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+
+WORKLOADS = {
+    # name: model, layers, dtype, batch, prefill tokens, decode steps
+    "llama2-7b-l0-7-fp32-b1-p512-d128": dict(model="7b", layers=8, dtype="f32", B=1, T=512, n_dec=128),
+    "llama2-7b-32l-bf16-b1-p1024-d256": dict(model="7b", layers=32, dtype="bf16", B=1, T=1024, n_dec=256),
+    "tiny-2l-fp32-b1-p32-d16": dict(model="tiny", layers=2, dtype="f32", B=1, T=32, n_dec=16),
+}
+DEFAULT_WORKLOAD = "llama2-7b-l0-7-fp32-b1-p512-d128"
+
+
+def algorithmic_work(cfg, wl):
+    """Bytes a decode step must move and FLOPs a prefill must do (weights once per step,
+    the causal half of attention only)."""
+    d, hq, hkv, dh, F = (cfg[k] for k in ("d_model", "n_heads", "n_kv_heads", "head_dim", "ffn_dim"))
+    L, B, T, n_dec = wl["layers"], wl["B"], wl["T"], wl["n_dec"]
+    e = 4 if wl["dtype"] == "f32" else 2
+    mat = 2 * d * hq * dh + 2 * d * hkv * dh + 3 * d * F            # matrix elements per layer
+    gains = 2 * d
+    mean_ctx = T + (n_dec + 1) / 2.0                                 # keys read by an average step
+    kv_tok = 2 * hkv * dh * e
+    decode_bytes = L * (mat * e + gains * 4) + B * L * kv_tok * (mean_ctx + 1) + 2 * B * d * 4
+    prefill_flops = 2.0 * B * T * L * mat + 2.0 * hq * dh * T * (T + 1) * L * B
+    linear_bytes = {  # per launch of the streaming projection kernel, by projection
+        "qkv": (hq + 2 * hkv) * dh * d * e, "o": d * hq * dh * e, "gate_up": 2 * F * d * e, "down": d * F * e,
+    }
+    gemm_flops = {k: 2.0 * B * T * v / e for k, v in linear_bytes.items()}
+    return dict(decode_bytes=decode_bytes, prefill_flops=prefill_flops, linear_bytes=linear_bytes,
+                gemm_flops=gemm_flops, weight_bytes=L * (mat * e + gains * 4))
+
+
+def cpu_baseline(cfg, wl, seed):
+    """Time the oracle, as it stands, on a bounded sample: 2 layers of the workload's layer
+    shape, a 32-token prefill and 6 decode steps; scale per-layer times to the shard."""
+    from threadpoolctl import threadpool_info
+    from oracle import llama_shard as orc
+    from paper_2405_14371_amd import synth
+    n_l, t_pre, n_dec = min(2, wl["layers"]), min(32, wl["T"]), 6
+    layers = synth.shard_weights(cfg, seed, 0, n_l, wl["dtype"])
+    o = orc.OracleShard(cfg, layers, keep_f64=True)
+    x = synth.hidden_states(cfg, seed, "prefill", 0, 0, 1, t_pre)[0].astype(np.float64)
+    t0 = time.perf_counter()
+    o.forward(0, x)
+    t_prefill = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    for s in range(n_dec):
+        o.forward(0, synth.hidden_states(cfg, seed, "dec", s, 0, 1, 1)[0].astype(np.float64))
+    t_dec = (time.perf_counter() - t0) / n_dec
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    scale = wl["layers"] / n_l
+    return {
+        "value": round(wl["B"] / (t_dec * scale), 4), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"{n_l} of {wl['layers']} layers of the workload's shape, {t_pre}-token prefill + {n_dec} decode "
+                  f"steps, batch 1; per-layer decode-step time scaled to {wl['layers']} layers",
+        "prefill_tokens_per_s": round(t_pre / (t_prefill * scale), 3),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS))
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs one shard on ONE GPU; --gpus > 1 is not supported "
+              "(a shard is a single device's share of the pipeline)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2405_14371_amd as pkg
+    from paper_2405_14371_amd import synth
+    lib = pkg.binding
+    lib.load()
+    torch.cuda.set_device(0)
+
+    wl = WORKLOADS[args.workload]
+    cfg = synth.model_cfg(wl["model"])
+    work = algorithmic_work(cfg, wl)
+    wd = lib.SHARD_F32 if wl["dtype"] == "f32" else lib.SHARD_BF16
+    B, T, n_dec, L = wl["B"], wl["T"], wl["n_dec"], wl["layers"]
+
+    t0 = time.perf_counter()
+    layers = synth.shard_weights(cfg, args.seed, 0, L, wl["dtype"])
+    sh = lib.Shard(cfg, lib.pack_layers(layers, wd), 0, weight_dtype=wd, max_seqs=B, max_seq_len=T + n_dec,
+                   page_size=16, max_batch_tokens=B * T)
+    del layers
+    x_pre = torch.from_numpy(np.concatenate(
+        [synth.hidden_states(cfg, args.seed, "prefill", 0, b, 1, T) for b in range(B)])).cuda()
+    x_dec = torch.from_numpy(np.stack(
+        [np.concatenate([synth.hidden_states(cfg, args.seed, "dec", s, b, 1, 1) for b in range(B)])
+         for s in range(n_dec)])).cuda()                      # [n_dec, B, 1, d]
+    y_pre = torch.empty_like(x_pre)
+    y_dec = torch.empty_like(x_dec)
+    setup_s = time.perf_counter() - t0
+
+    stream = torch.cuda.current_stream()
+    st = stream.cuda_stream
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def one_step(timed):
+        ids = [sh.seq_alloc() for _ in range(B)]
+        e0, e1, e2 = ev(), ev(), ev()
+        e0.record(stream)
+        sh.prefill(ids, T, x_pre, y_pre, st)
+        e1.record(stream)
+        for s in range(n_dec):
+            sh.decode(ids, x_dec[s], y_dec[s], st)
+        e2.record(stream)
+        torch.cuda.synchronize()
+        for i in ids:
+            sh.seq_free(i)
+        return (e0.elapsed_time(e1) * 1e-3, e1.elapsed_time(e2) * 1e-3) if timed else None
+
+    for _ in range(args.warmup):
+        one_step(False)
+    torch.cuda.synchronize()
+    t_wall0 = time.perf_counter()
+    times = [one_step(True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_wall0
+    assert torch.isfinite(y_dec).all() and torch.isfinite(y_pre).all()
+
+    t_pre = sum(t[0] for t in times)
+    t_dec = sum(t[1] for t in times)
+    dec_tok_s = B * n_dec * args.steps / t_dec
+    dec_gbps = work["decode_bytes"] * n_dec * args.steps / t_dec / 1e9
+    pre_tflops = work["prefill_flops"] * args.steps / t_pre / 1e12
+
+    # one more step with HIP events around every launch, for the per-kernel roofline
+    sh.timing_enable(True)
+    one_step(False)
+    kt = sh.timing_read()
+    sh.timing_enable(False)
+    lin = kt["decode_linear"]
+    lin_bytes = sum(work["linear_bytes"].values()) * L * n_dec
+    lin_gbps = lin_bytes / lin["seconds"] / 1e9
+    roofline = {
+        "kernel": "decode_linear_kernel (weight-streaming projections of shard_decode)",
+        "bound": "hbm", "achieved": round(lin_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": round(lin_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+        "launches": lin["launches"], "avg_launch_us": round(lin["seconds"] / max(1, lin["launches"]) * 1e6, 2),
+        "algorithmic_bytes_per_launch": round(lin_bytes / max(1, lin["launches"])),
+    }
+    gm = kt["prefill_gemm"]
+    gm_flops = sum(work["gemm_flops"].values()) * L
+    peak_tf = MFMA_PEAK_TFLOPS[wl["dtype"]]
+    roofline_prefill = {
+        "kernel": "gemm_kernel (MFMA projections of shard_prefill)",
+        "bound": "mfma", "achieved": round(gm_flops / gm["seconds"] / 1e12, 2), "peak": peak_tf, "unit": "TFLOP/s",
+        "frac": round(gm_flops / gm["seconds"] / 1e12 / peak_tf, 4),
+        "launches": gm["launches"], "avg_launch_us": round(gm["seconds"] / max(1, gm["launches"]) * 1e6, 2),
+    }
+    kernel_seconds = {k: {"launches": v["launches"], "ms": round(v["seconds"] * 1e3, 3)} for k, v in kt.items()}
+    sh.close()
+
+    out = {
+        "metric": "shard_decode_tokens_per_s",
+        "value": round(dec_tok_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round((t_pre + t_dec) / args.steps * 1e3, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": wl["dtype"], "data": "synthetic",
+        "config": {"workload": args.workload, "layers": L, "batch": B, "prefill_tokens": T, "decode_steps": n_dec,
+                   "page_size": 16, "seed": args.seed},
+        "decode_ms_per_token": round(t_dec / (n_dec * args.steps) * 1e3, 4),
+        "decode_gbps": round(dec_gbps, 1), "decode_hbm_frac": round(dec_gbps / HBM_PEAK_GBPS, 4),
+        "prefill_ms": round(t_pre / args.steps * 1e3, 3),
+        "prefill_tokens_per_s": round(B * T * args.steps / t_pre, 1),
+        "prefill_tflops": round(pre_tflops, 2), "prefill_mfma_frac": round(pre_tflops / peak_tf, 4),
+        "roofline": roofline, "roofline_prefill": roofline_prefill, "kernel_ms_instrumented_step": kernel_seconds,
+        "wall_s_timed_region": round(wall, 3), "setup_s": round(setup_s, 1),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, wl, args.seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

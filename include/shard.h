@@ -1,0 +1,169 @@
+/*
+ * libshard - forward pass of one EdgeShard shard on one MI355X (gfx950).
+ *
+ * A shard is a contiguous range [layer_lo, layer_hi) of a model's decoder layers placed on
+ * one device; the device receives the previous range's output activations, runs its
+ * layers over a KV cache it pre-allocated, and hands its own output activations on
+ * (EdgeShard Sec. 3 "Collaborative inference"; Sec. 4 "System Model": layer i has an
+ * activation size O_i and a memory need Req_i).  Inference has two phases: prefill
+ * consumes the whole prompt at once, the autoregressive phase consumes one token per
+ * iteration and reuses the cached keys/values (Sec. 2 "Generative LLM Inference").
+ *
+ * The layer is the Llama 2 decoder layer (the model family of Sec. 5.1): pre-norm
+ * RMSNorm (eps inside the root, gain after), bias-free Q/K/V/O projections, rotary
+ * position embedding on ADJACENT element pairs (2i, 2i+1) of every q/k head with angle
+ * pos * theta^(-2i/head_dim), causal softmax attention scaled by 1/sqrt(head_dim) where
+ * query head h reads KV head h / (n_heads / n_kv_heads), residual add, RMSNorm,
+ * SwiGLU feed-forward silu(Wg h) * (Wu h) -> Wd, residual add.
+ *
+ * Conventions for every entry point
+ *  - Return value: SHARD_OK or a negative SHARD_E_* code; shard_last_error() gives a
+ *    thread-local human-readable message for the last failure on the calling thread.
+ *    Nothing throws or aborts across this boundary.  Validation happens before any
+ *    launch; a call that fails validation leaves the shard unchanged.
+ *  - "device pointer" = memory of the current HIP device; "host pointer" = ordinary
+ *    host memory.  The library never takes ownership of caller memory.
+ *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *    enqueued on it and the call returns without waiting; the caller synchronises.
+ *  - A shard handle is not thread-safe; use one thread per handle at a time.
+ */
+#ifndef SHARD_H
+#define SHARD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct shard shard_t; /* opaque; created by shard_create, freed by shard_destroy */
+
+enum {
+    SHARD_OK = 0,
+    SHARD_E_INVAL = -1,   /* bad argument or configuration */
+    SHARD_E_NOMEM = -2,   /* device or host allocation failed */
+    SHARD_E_KV_FULL = -3, /* sequence would exceed max_seq_len, or no free sequence slot */
+    SHARD_E_STATE = -4,   /* unknown seq_id, decode on an empty sequence, duplicate seq_id */
+    SHARD_E_HIP = -5      /* a HIP runtime call failed */
+};
+
+enum { SHARD_F32 = 0, SHARD_BF16 = 1 };
+
+/* Largest number of sequences one shard_prefill / shard_decode call may carry. */
+#define SHARD_MAX_BATCH 64
+
+typedef struct {
+    int32_t d_model;      /* width of the hidden state */
+    int32_t n_heads;      /* query heads Hq */
+    int32_t n_kv_heads;   /* key/value heads Hkv; must divide n_heads */
+    int32_t head_dim;     /* dh: 32, 64 or 128 */
+    int32_t ffn_dim;      /* SwiGLU inner width F */
+    float rms_eps;
+    float rope_theta;
+    int32_t weight_dtype; /* SHARD_F32 or SHARD_BF16: dtype of the matrices AND of the KV cache */
+    int32_t act_dtype;    /* dtype of x_in / x_out at the boundary; only SHARD_F32 is supported:
+                             the paper runs full precision, and an fp32 hand-off keeps shard
+                             composition exact.  The residual stream inside is always fp32. */
+} shard_model_cfg;
+
+typedef struct {
+    int32_t max_seqs;         /* sequences that can be live at once (>= 1) */
+    int32_t max_seq_len;      /* tokens per sequence the cache can hold (>= 1) */
+    int32_t page_size;        /* tokens per KV page (>= 1; 16 is the tuned value) */
+    int32_t max_batch_tokens; /* largest B*T of one shard_prefill call; 0 = max_seq_len */
+} shard_kv_cfg;
+
+/* One layer's parameters.  Matrices are [out, in] row-major in weight_dtype (bf16 as raw
+ * 16-bit patterns): wq [Hq*dh, d], wk/wv [Hkv*dh, d], wo [d, Hq*dh], w_gate/w_up [F, d],
+ * w_down [d, F].  Gains g_attn, g_ffn are float32 [d]. */
+typedef struct {
+    const void *wq, *wk, *wv, *wo, *w_gate, *w_up, *w_down;
+    const float *g_attn, *g_ffn;
+} shard_layer_weights;
+
+/* What offline profiling records per layer (Sec. 3 "Profiling": execution time of each
+ * layer for the prefill and the autoregressive stage and their average; activation size;
+ * memory consumption).  Times are seconds per call of that layer. */
+typedef struct {
+    double t_prefill_s;         /* mean time of the layer in a prefill of (B, T_prefill) */
+    double t_decode_s;          /* mean time of the layer in one decode step at batch B */
+    double t_avg_s;             /* mean time per generated token over 1 prefill + n_decode steps:
+                                   (t_prefill_s + n_decode * t_decode_s) / (1 + n_decode) */
+    uint64_t act_bytes_prefill; /* O_i for the profiled prefill: B * T_prefill * d * 4 */
+    uint64_t act_bytes_decode;  /* O_i for one decode step: B * d * 4 */
+    uint64_t weight_bytes;      /* Req_i, parameter part */
+    uint64_t kv_bytes_per_token;/* Req_i, cache part per cached token: 2 * Hkv * dh * sizeof(dtype) */
+} shard_layer_profile;
+
+/* Build a shard for layers [layer_lo, layer_hi) (0 <= layer_lo < layer_hi; the indices
+ * only label the range - `w` holds layer_hi - layer_lo entries, entry 0 being layer_lo).
+ * Copies (and repacks) all weights into library-owned device memory and pre-allocates the
+ * KV page pool (max_seqs * ceil(max_seq_len / page_size) pages per layer for K and V) and
+ * all workspace (Sec. 3: the KV cache is pre-allocated on each participating device);
+ * the caller may free its weight buffers when the call returns.
+ * weights_on_device: 0 = the pointers in `w` are host pointers, 1 = device pointers.
+ * Blocks until the upload is complete.  On failure *out is NULL. */
+int shard_create(shard_t **out, const shard_model_cfg *model, const shard_kv_cfg *kv,
+                 int32_t layer_lo, int32_t layer_hi, const shard_layer_weights *w,
+                 int32_t weights_on_device);
+
+/* Wait for the shard's outstanding work and release everything it owns.  NULL is OK. */
+int shard_destroy(shard_t *s);
+
+/* Reserve a sequence slot (an empty KV cache row); *seq_id receives its id.
+ * SHARD_E_KV_FULL when max_seqs are live. */
+int shard_seq_alloc(shard_t *s, int32_t *seq_id);
+
+/* Return a sequence's pages to the pool.  Work already enqueued that uses the sequence
+ * must have completed.  SHARD_E_STATE for an id that is not live. */
+int shard_seq_free(shard_t *s, int32_t seq_id);
+
+/* Tokens currently cached for a live sequence, or a negative error code. */
+int32_t shard_seq_len(shard_t *s, int32_t seq_id);
+
+/* Prefill phase (Sec. 2): append T tokens to each of the B distinct sequences seq_ids[0..B)
+ * (host pointer) and produce the range's output activation for every token.
+ * x_in, x_out: device pointers, float32 [B, T, d_model] row-major; x_out may alias x_in.
+ * Sequence b's tokens take positions P_b .. P_b+T-1 where P_b is its current length, so a
+ * non-empty sequence is legal (chunked prefill).  1 <= B <= SHARD_MAX_BATCH,
+ * B*T <= max_batch_tokens, P_b + T <= max_seq_len (else SHARD_E_KV_FULL). */
+int shard_prefill(shard_t *s, const int32_t *seq_ids, int32_t B, int32_t T,
+                  const void *x_in, void *x_out, void *hip_stream);
+
+/* Autoregressive phase (Sec. 2): one new token for each of the B distinct sequences, each
+ * of which must already hold at least one token (SHARD_E_STATE otherwise); lengths may
+ * differ between sequences.  x_in, x_out: device pointers, float32 [B, d_model]. */
+int shard_decode(shard_t *s, const int32_t *seq_ids, int32_t B,
+                 const void *x_in, void *x_out, void *hip_stream);
+
+/* Offline profiling of this device's column of the planner's inputs (Sec. 3 "Profiling"):
+ * on scratch sequences and zero-free synthetic activations, time every layer of the range
+ * with HIP events in a prefill of (B, T_prefill) and in n_decode following decode steps,
+ * averaged over `iters` repetitions, and report activation and memory sizes.
+ * Needs B free sequence slots; blocks until done; `out` is a host array of
+ * layer_hi - layer_lo entries. */
+int shard_profile(shard_t *s, int32_t B, int32_t T_prefill, int32_t n_decode, int32_t iters,
+                  shard_layer_profile *out);
+
+/* Kernel timing for roofline reports.  While enabled, every launch of the kernel classes
+ * below is bracketed by HIP events on its stream; shard_timing_read waits for the stream
+ * work recorded so far, and returns launches and total seconds per class since enable.
+ * Classes follow the steps of the layer; see SHARD_K_* . */
+enum {
+    SHARD_K_DECODE_LINEAR = 0, /* weight-streaming projections of shard_decode (QKV, O, gate/up, down) */
+    SHARD_K_DECODE_ATTN = 1,
+    SHARD_K_PREFILL_GEMM = 2,  /* MFMA projections of shard_prefill */
+    SHARD_K_PREFILL_ATTN = 3,
+    SHARD_K_OTHER = 4,         /* RMSNorm and bookkeeping kernels */
+    SHARD_K_COUNT = 5
+};
+int shard_timing_enable(shard_t *s, int32_t on);
+int shard_timing_read(shard_t *s, int64_t launches[SHARD_K_COUNT], double seconds[SHARD_K_COUNT]);
+
+/* Message for the most recent failure on this thread ("" if none). */
+const char *shard_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SHARD_H */

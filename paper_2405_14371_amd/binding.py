@@ -1,0 +1,205 @@
+"""ctypes binding of libshard.so: the same entry points as include/shard.h, argument
+marshalling only.  PyTorch supplies device buffers and streams; every step of the layer
+runs in the library's HIP kernels.  There is no fallback: a missing library is an error."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libshard.so")
+
+SHARD_OK, SHARD_E_INVAL, SHARD_E_NOMEM, SHARD_E_KV_FULL, SHARD_E_STATE, SHARD_E_HIP = 0, -1, -2, -3, -4, -5
+SHARD_F32, SHARD_BF16 = 0, 1
+SHARD_MAX_BATCH = 64
+K_DECODE_LINEAR, K_DECODE_ATTN, K_PREFILL_GEMM, K_PREFILL_ATTN, K_OTHER, K_COUNT = 0, 1, 2, 3, 4, 5
+KERNEL_CLASSES = ("decode_linear", "decode_attn", "prefill_gemm", "prefill_attn", "other")
+
+EXPORTS = (
+    "shard_create", "shard_destroy", "shard_seq_alloc", "shard_seq_free", "shard_seq_len",
+    "shard_prefill", "shard_decode", "shard_profile", "shard_timing_enable", "shard_timing_read",
+    "shard_last_error",
+)
+
+
+class ModelCfg(C.Structure):
+    _fields_ = [("d_model", C.c_int32), ("n_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("ffn_dim", C.c_int32), ("rms_eps", C.c_float),
+                ("rope_theta", C.c_float), ("weight_dtype", C.c_int32), ("act_dtype", C.c_int32)]
+
+
+class KvCfg(C.Structure):
+    _fields_ = [("max_seqs", C.c_int32), ("max_seq_len", C.c_int32), ("page_size", C.c_int32),
+                ("max_batch_tokens", C.c_int32)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "g_attn", "g_ffn")]
+
+
+class LayerProfile(C.Structure):
+    _fields_ = [("t_prefill_s", C.c_double), ("t_decode_s", C.c_double), ("t_avg_s", C.c_double),
+                ("act_bytes_prefill", C.c_uint64), ("act_bytes_decode", C.c_uint64),
+                ("weight_bytes", C.c_uint64), ("kv_bytes_per_token", C.c_uint64)]
+
+
+class ShardError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"libshard error {code}: {message}")
+        self.code = code
+
+
+_lib = None
+
+
+def load():
+    """Load libshard.so (built in-tree by build.py) and declare its signatures."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2405_14371_amd.build` "
+                           "(or __graft_entry__.build()) first; there is no CPU fallback")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32 = C.c_void_p, C.c_int32
+    lib.shard_create.argtypes = [C.POINTER(vp), C.POINTER(ModelCfg), C.POINTER(KvCfg), i32, i32,
+                                 C.POINTER(LayerWeights), i32]
+    lib.shard_destroy.argtypes = [vp]
+    lib.shard_seq_alloc.argtypes = [vp, C.POINTER(i32)]
+    lib.shard_seq_free.argtypes = [vp, i32]
+    lib.shard_seq_len.argtypes = [vp, i32]
+    lib.shard_prefill.argtypes = [vp, C.POINTER(i32), i32, i32, vp, vp, vp]
+    lib.shard_decode.argtypes = [vp, C.POINTER(i32), i32, vp, vp, vp]
+    lib.shard_profile.argtypes = [vp, i32, i32, i32, i32, C.POINTER(LayerProfile)]
+    lib.shard_timing_enable.argtypes = [vp, i32]
+    lib.shard_timing_read.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+    lib.shard_last_error.argtypes = []
+    lib.shard_last_error.restype = C.c_char_p
+    for name in EXPORTS:
+        if name != "shard_last_error":
+            getattr(lib, name).restype = i32
+    _lib = lib
+    return lib
+
+
+def last_error() -> str:
+    return load().shard_last_error().decode()
+
+
+def _check(rc: int) -> int:
+    if rc < 0:
+        raise ShardError(rc, last_error())
+    return rc
+
+
+def _ptr(t) -> int:
+    """Raw pointer of a torch tensor, a numpy array or an int."""
+    if t is None:
+        return 0
+    if isinstance(t, int):
+        return t
+    if isinstance(t, np.ndarray):
+        return t.ctypes.data
+    return t.data_ptr()
+
+
+def _ids(seq_ids):
+    arr = (C.c_int32 * len(seq_ids))(*[int(i) for i in seq_ids])
+    return arr, len(seq_ids)
+
+
+def model_cfg(cfg: dict, weight_dtype: int) -> ModelCfg:
+    return ModelCfg(cfg["d_model"], cfg["n_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["ffn_dim"],
+                    cfg["rms_eps"], cfg["rope_theta"], weight_dtype, SHARD_F32)
+
+
+class Shard:
+    """One shard on the current device.  `layers` is a list of dicts of host numpy arrays
+    (float32 for SHARD_F32, uint16 bf16 bit patterns for SHARD_BF16; gains float32) or of
+    torch device tensors of the matching element size (on_device=True)."""
+
+    def __init__(self, cfg: dict, layers: list, layer_lo: int = 0, *, weight_dtype: int = SHARD_F32,
+                 max_seqs: int = 1, max_seq_len: int = 2048, page_size: int = 16,
+                 max_batch_tokens: int = 0, on_device: bool = False):
+        self._h = C.c_void_p()
+        self.cfg = dict(cfg)
+        self.n_layers = len(layers)
+        lib = load()
+        mc = model_cfg(cfg, weight_dtype)
+        kc = KvCfg(max_seqs, max_seq_len, page_size, max_batch_tokens)
+        arr = (LayerWeights * max(1, len(layers)))()
+        keep = []
+        for i, lw in enumerate(layers):
+            for name, _ in LayerWeights._fields_:
+                t = lw[name]
+                if isinstance(t, np.ndarray):
+                    want = np.float32 if (name.startswith("g_") or weight_dtype == SHARD_F32) else np.uint16
+                    if t.dtype != want:
+                        raise TypeError(f"{name}: expected {want.__name__}, got {t.dtype}")
+                    t = np.ascontiguousarray(t)
+                keep.append(t)
+                setattr(arr[i], name, _ptr(t))
+        _check(lib.shard_create(C.byref(self._h), C.byref(mc), C.byref(kc), layer_lo, layer_lo + len(layers),
+                                arr, 1 if on_device else 0))
+
+    def close(self):
+        if self._h:
+            _check(load().shard_destroy(self._h))
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def seq_alloc(self) -> int:
+        out = C.c_int32(-1)
+        _check(load().shard_seq_alloc(self._h, C.byref(out)))
+        return out.value
+
+    def seq_free(self, seq_id: int) -> None:
+        _check(load().shard_seq_free(self._h, seq_id))
+
+    def seq_len(self, seq_id: int) -> int:
+        return _check(load().shard_seq_len(self._h, seq_id))
+
+    def prefill(self, seq_ids, T: int, x_in, x_out, stream: int = 0) -> None:
+        ids, n = _ids(seq_ids)
+        _check(load().shard_prefill(self._h, ids, n, T, _ptr(x_in), _ptr(x_out), stream))
+
+    def decode(self, seq_ids, x_in, x_out, stream: int = 0) -> None:
+        ids, n = _ids(seq_ids)
+        _check(load().shard_decode(self._h, ids, n, _ptr(x_in), _ptr(x_out), stream))
+
+    def profile(self, B: int, T_prefill: int, n_decode: int, iters: int = 3) -> list:
+        out = (LayerProfile * self.n_layers)()
+        _check(load().shard_profile(self._h, B, T_prefill, n_decode, iters, out))
+        return [{f: getattr(p, f) for f, _ in LayerProfile._fields_} for p in out]
+
+    def timing_enable(self, on: bool = True) -> None:
+        _check(load().shard_timing_enable(self._h, 1 if on else 0))
+
+    def timing_read(self) -> dict:
+        n = (C.c_int64 * K_COUNT)()
+        s = (C.c_double * K_COUNT)()
+        _check(load().shard_timing_read(self._h, n, s))
+        return {KERNEL_CLASSES[k]: {"launches": n[k], "seconds": s[k]} for k in range(K_COUNT)}
+
+
+def pack_layers(layers: list, weight_dtype: int) -> list:
+    """float32 host arrays from synth -> the element type the library expects."""
+    from .synth import bf16_bits
+    out = []
+    for lw in layers:
+        d = {}
+        for k, v in lw.items():
+            if k.startswith("g_") or weight_dtype == SHARD_F32:
+                d[k] = np.ascontiguousarray(v, dtype=np.float32)
+            else:
+                d[k] = bf16_bits(v)
+        out.append(d)
+    return out

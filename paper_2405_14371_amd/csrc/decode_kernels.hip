@@ -1,0 +1,332 @@
+// Autoregressive-phase kernels (EdgeShard Sec. 2: one token per iteration over the KV
+// cache).  Every weight is read exactly once per step, so these kernels are HBM streams:
+// 16-byte loads per lane, many independent loads in flight, fixed-order reductions.
+#include "kernels.hpp"
+
+namespace shk {
+
+// ---------------------------------------------------------------------------------------
+// Linear layer for nb <= NB activation rows.  One workgroup (256 threads) owns R
+// consecutive output rows of W and the whole K extent: thread t covers the 16-byte chunks
+// t, t+256, ... of every one of its R rows, so each chunk of x is loaded once and reused
+// for R rows.  U chunks are fetched per trip so that U*R independent 16-byte loads per
+// lane are in flight.  Partial sums are reduced across the wave with shuffles, across the
+// four waves through LDS, always in the same order.
+// ---------------------------------------------------------------------------------------
+template <typename WT, int NB, int R, int U>
+__global__ __launch_bounds__(256) void decode_linear_kernel(DecodeLinear a, SeqBatch sb) {
+    constexpr int VEC = Elem<WT>::VEC;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row0 = blockIdx.x * R;
+    const int nchunk = a.K / VEC;
+    const WT* __restrict__ W = static_cast<const WT*>(a.W);
+    const bool norm = a.gain != nullptr;
+
+    __shared__ float s_red[4][R * NB];
+    __shared__ float s_ssq[4][NB];
+    __shared__ float s_val[R * NB];
+
+    float acc[R][NB];
+    float ssq[NB];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) acc[r][b] = 0.f;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) ssq[b] = 0.f;
+
+    const WT* rowp[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int n = min(row0 + r, a.N - 1);  // rows past N re-read the last row; never stored
+        rowp[r] = W + static_cast<size_t>(n) * a.K;
+    }
+
+    for (int c0 = tid; c0 < nchunk; c0 += 256 * U) {
+        Vec16<WT> w[U][R];
+        int cc[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + 256 * u;
+            ok[u] = c < nchunk;
+            cc[u] = ok[u] ? c : c0;
+#pragma unroll
+            for (int r = 0; r < R; ++r) w[u][r].load(rowp[r] + static_cast<size_t>(cc[u]) * VEC);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float xv[NB][VEC];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const float* xp = a.x + static_cast<size_t>(b < a.nb ? b : 0) * a.K + cc[u] * VEC;
+#pragma unroll
+                for (int e = 0; e < VEC; e += 4) {
+                    const float4 t = *reinterpret_cast<const float4*>(xp + e);
+                    xv[b][e] = t.x; xv[b][e + 1] = t.y; xv[b][e + 2] = t.z; xv[b][e + 3] = t.w;
+                }
+            }
+            if (!ok[u]) {
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) xv[b][e] = 0.f;
+            }
+            if (norm) {
+                float g[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; e += 4) {
+                    const float4 t = *reinterpret_cast<const float4*>(a.gain + cc[u] * VEC + e);
+                    g[e] = t.x; g[e + 1] = t.y; g[e + 2] = t.z; g[e + 3] = t.w;
+                }
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        ssq[b] = fmaf(xv[b][e], xv[b][e], ssq[b]);
+                        xv[b][e] *= g[e];
+                    }
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) acc[r][b] = fmaf(w[u][r].v[e], xv[b][e], acc[r][b]);
+        }
+    }
+
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const float v = wave_sum(acc[r][b]);
+            if (lane == 0) s_red[wave][r * NB + b] = v;
+        }
+    if (norm) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const float v = wave_sum(ssq[b]);
+            if (lane == 0) s_ssq[wave][b] = v;
+        }
+    }
+    __syncthreads();
+    if (tid < R * NB) {
+        float v = (s_red[0][tid] + s_red[1][tid]) + (s_red[2][tid] + s_red[3][tid]);
+        if (norm) {
+            const int b = tid % NB;
+            const float ms = ((s_ssq[0][b] + s_ssq[1][b]) + (s_ssq[2][b] + s_ssq[3][b])) / static_cast<float>(a.K);
+            v *= 1.0f / sqrtf(ms + a.eps);
+        }
+        s_val[tid] = v;
+    }
+    __syncthreads();
+
+    if (a.epi == EPI_RESID) {
+        if (tid < R * NB) {
+            const int r = tid / NB, b = tid % NB, n = row0 + r;
+            if (n < a.N && b < a.nb) {
+                const size_t i = static_cast<size_t>(b) * a.N + n;
+                a.out[i] = a.resid[i] + s_val[tid];
+            }
+        }
+        return;
+    }
+    // the other epilogues work on row pairs (2j, 2j+1)
+    if (tid >= (R / 2) * NB) return;
+    const int j = tid / NB, b = tid % NB;
+    const int n0 = row0 + 2 * j;
+    if (n0 >= a.N || b >= a.nb) return;
+    const float v0 = s_val[(2 * j) * NB + b], v1 = s_val[(2 * j + 1) * NB + b];
+    if (a.epi == EPI_SWIGLU) {
+        const int F = a.N / 2;
+        a.out[static_cast<size_t>(b) * F + n0 / 2] = v0 / (1.0f + expf(-v0)) * v1;
+        return;
+    }
+    // EPI_QKV
+    const int dh = a.kv.dh, nq = a.hq * dh, nk = a.kv.hkv * dh;
+    const int pos = sb.pos[b];
+    if (n0 < nq + nk) {  // q or k: rotate the pair
+        const int e = n0 % dh;
+        const float2 cs = a.rope[static_cast<size_t>(pos) * (dh / 2) + e / 2];
+        const float r0 = v0 * cs.x - v1 * cs.y, r1 = v0 * cs.y + v1 * cs.x;
+        if (n0 < nq) {
+            a.q[static_cast<size_t>(b) * nq + n0] = r0;
+            a.q[static_cast<size_t>(b) * nq + n0 + 1] = r1;
+            return;
+        }
+        const int hk = (n0 - nq) / dh;
+        const int page = a.kv.block_table[sb.seq[b] * a.kv.max_pages + pos / a.kv.page];
+        const size_t at = ((static_cast<size_t>(page) * a.kv.hkv + hk) * a.kv.page + pos % a.kv.page) * dh + e;
+        WT* kp = static_cast<WT*>(a.kv.k);
+        kp[at] = Elem<WT>::from_f32(r0);
+        kp[at + 1] = Elem<WT>::from_f32(r1);
+        return;
+    }
+    {
+        const int hk = (n0 - nq - nk) / dh, e = n0 % dh;
+        const int page = a.kv.block_table[sb.seq[b] * a.kv.max_pages + pos / a.kv.page];
+        const size_t at = ((static_cast<size_t>(page) * a.kv.hkv + hk) * a.kv.page + pos % a.kv.page) * dh + e;
+        WT* vp = static_cast<WT*>(a.kv.v);
+        vp[at] = Elem<WT>::from_f32(v0);
+        vp[at + 1] = Elem<WT>::from_f32(v1);
+    }
+}
+
+template <typename WT, int NB, int R, int U>
+static void launch_dl(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
+    const int grid = (a.N + R - 1) / R;
+    hipLaunchKernelGGL((decode_linear_kernel<WT, NB, R, U>), dim3(grid), dim3(256), 0, st, a, sb);
+}
+
+template <typename WT>
+static void launch_dl_t(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
+    if (a.nb == 1) launch_dl<WT, 1, 4, 4>(a, sb, st);
+    else if (a.nb == 2) launch_dl<WT, 2, 4, 2>(a, sb, st);
+    else if (a.nb <= 4) launch_dl<WT, 4, 4, 2>(a, sb, st);
+    else launch_dl<WT, 8, 4, 1>(a, sb, st);
+}
+
+void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
+    if (a.wt == DT_F32) launch_dl_t<float>(a, sb, st);
+    else launch_dl_t<bf16_t>(a, sb, st);
+}
+
+// ---------------------------------------------------------------------------------------
+// Attention of one new token per sequence over its cached keys/values.
+// Grid (nsplit, nb*hq).  A workgroup takes one slice of the context of one (sequence,
+// query head); TPT = DH/VEC adjacent lanes share a token (one 16-byte load each), so a
+// workgroup handles 256/TPT tokens per trip.  Each lane group keeps its own running
+// (max, sum, weighted V) - softmax statistics are merged with lane shuffles inside the
+// group, through LDS across groups, and across context slices by the workgroup that
+// finishes last (fixed slice order, so the result does not depend on which one that is).
+// ---------------------------------------------------------------------------------------
+template <typename KT, int DH>
+__global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttn a, SeqBatch sb) {
+    constexpr int VEC = Elem<KT>::VEC;
+    constexpr int TPT = DH / VEC;
+    constexpr int GROUPS = 256 / TPT;
+    const int tid = threadIdx.x;
+    const int split = blockIdx.x, bh = blockIdx.y;
+    const int b = bh / a.hq, h = bh % a.hq;
+    const int hk = h / (a.hq / a.kv.hkv);
+    const int seq = sb.seq[b];
+    const int ctx = sb.pos[b] + 1;  // the new token's k,v are already in the cache
+    const int per = (ctx + a.nsplit - 1) / a.nsplit;
+    const int u_begin = split * per, u_end = min(ctx, u_begin + per);
+    const int g = tid / TPT, e0 = (tid % TPT) * VEC;
+    const float scale = 1.0f / sqrtf(static_cast<float>(DH));
+    const KT* __restrict__ kp = static_cast<const KT*>(a.kv.k);
+    const KT* __restrict__ vp = static_cast<const KT*>(a.kv.v);
+    const int32_t* bt = a.kv.block_table + static_cast<size_t>(seq) * a.kv.max_pages;
+
+    float qv[VEC];
+    {
+        const float* qp = a.q + static_cast<size_t>(b) * a.hq * DH + h * DH + e0;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) qv[e] = qp[e] * scale;
+    }
+    float m = -INFINITY, l = 0.f, acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+
+    for (int u = u_begin + g; u < u_end; u += GROUPS) {
+        const int page = bt[u / a.kv.page];
+        const size_t at = ((static_cast<size_t>(page) * a.kv.hkv + hk) * a.kv.page + u % a.kv.page) * DH + e0;
+        Vec16<KT> kv, vv;
+        kv.load(kp + at);
+        vv.load(vp + at);
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) s = fmaf(qv[e], kv.v[e], s);
+#pragma unroll
+        for (int o = TPT / 2; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+        const float mn = fmaxf(m, s);
+        const float corr = __expf(m - mn), p = __expf(s - mn);
+        l = l * corr + p;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = fmaf(p, vv.v[e], acc[e] * corr);
+        m = mn;
+    }
+
+    __shared__ float s_m[GROUPS], s_l[GROUPS];
+    __shared__ float s_acc[GROUPS][DH];
+    __shared__ int s_ticket;
+    if (tid % TPT == 0) { s_m[g] = m; s_l[g] = l; }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) s_acc[g][e0 + e] = acc[e];
+    __syncthreads();
+
+    float M = -INFINITY, L = 0.f, O = 0.f;
+    if (tid < DH) {
+        for (int i = 0; i < GROUPS; ++i) M = fmaxf(M, s_m[i]);
+        if (M > -INFINITY) {
+            for (int i = 0; i < GROUPS; ++i) {
+                const float w = __expf(s_m[i] - M);  // empty groups: exp(-inf) = 0
+                L = fmaf(s_l[i], w, L);
+                O = fmaf(s_acc[i][tid], w, O);
+            }
+        }
+    }
+    float* op = a.o + static_cast<size_t>(b) * a.hq * DH + h * DH;
+    if (a.nsplit == 1) {
+        if (tid < DH) op[tid] = O / L;
+        return;
+    }
+    const size_t pbase = static_cast<size_t>(bh) * a.nsplit;
+    if (tid < DH) a.part_o[(pbase + split) * DH + tid] = O;
+    if (tid == 0) {
+        a.part_ml[(pbase + split) * 2] = M;
+        a.part_ml[(pbase + split) * 2 + 1] = L;
+    }
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) s_ticket = atomicAdd(&a.counters[bh], 1);
+    __syncthreads();
+    if (s_ticket != a.nsplit - 1) return;
+    __threadfence();
+    if (tid < DH) {
+        float Mx = -INFINITY;
+        for (int s = 0; s < a.nsplit; ++s) Mx = fmaxf(Mx, a.part_ml[(pbase + s) * 2]);
+        float Lx = 0.f, Ox = 0.f;
+        for (int s = 0; s < a.nsplit; ++s) {
+            const float ms = a.part_ml[(pbase + s) * 2];
+            if (ms == -INFINITY) continue;  // slice held no tokens
+            const float w = __expf(ms - Mx);
+            Lx = fmaf(a.part_ml[(pbase + s) * 2 + 1], w, Lx);
+            Ox = fmaf(a.part_o[(pbase + s) * DH + tid], w, Ox);
+        }
+        op[tid] = Ox / Lx;
+    }
+    if (tid == 0) a.counters[bh] = 0;
+}
+
+void launch_decode_attn(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st) {
+    const dim3 grid(a.nsplit, a.nb * a.hq), block(256);
+    const bool f32 = a.kv_dtype == DT_F32;
+    switch (a.kv.dh) {
+        case 32:
+            if (f32) hipLaunchKernelGGL((decode_attn_kernel<float, 32>), grid, block, 0, st, a, sb);
+            else hipLaunchKernelGGL((decode_attn_kernel<bf16_t, 32>), grid, block, 0, st, a, sb);
+            break;
+        case 64:
+            if (f32) hipLaunchKernelGGL((decode_attn_kernel<float, 64>), grid, block, 0, st, a, sb);
+            else hipLaunchKernelGGL((decode_attn_kernel<bf16_t, 64>), grid, block, 0, st, a, sb);
+            break;
+        default:
+            if (f32) hipLaunchKernelGGL((decode_attn_kernel<float, 128>), grid, block, 0, st, a, sb);
+            else hipLaunchKernelGGL((decode_attn_kernel<bf16_t, 128>), grid, block, 0, st, a, sb);
+            break;
+    }
+}
+
+__global__ void table_update_kernel(int32_t* table, TableUpdate u) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < u.n) table[u.idx[i]] = u.val[i];
+}
+
+void launch_table_update(int32_t* table, const TableUpdate& u, hipStream_t st) {
+    hipLaunchKernelGGL(table_update_kernel, dim3(1), dim3(128), 0, st, table, u);
+}
+
+}  // namespace shk

@@ -1,0 +1,106 @@
+// Host-side launch interface of the gfx950 kernels.  Every function validates nothing:
+// the runtime (shard.cpp) checks shapes before it calls them.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "device_utils.hpp"
+
+namespace shk {
+
+enum DType { DT_F32 = 0, DT_BF16 = 1 };
+
+// One layer's paged KV cache.  Element (page p, kv head h, slot s, e) of K or V lives at
+// ((p * hkv + h) * page + s) * dh + e; token u of sequence q is in page
+// block_table[q * max_pages + u / page], slot u % page.
+struct KvView {
+    void* k;
+    void* v;
+    const int32_t* block_table;
+    int32_t max_pages, page, hkv, dh;
+};
+
+enum Epilogue {
+    EPI_QKV = 0,     // RoPE on q,k; q -> q buffer (fp32); k,v -> cache pages
+    EPI_RESID = 1,   // out = resid + acc   (fp32)
+    EPI_SWIGLU = 2   // rows (2f, 2f+1) = (gate_f, up_f): out[f] = silu(gate) * up
+};
+
+// y = W x for a few activation rows (decode): W [N, K] row-major (dtype wt), x fp32 [nb, K].
+struct DecodeLinear {
+    const void* W;
+    int32_t N, K;
+    int32_t wt;            // DType of W
+    int32_t nb;            // activation rows, 1..8
+    const float* x;        // [nb, K]
+    const float* gain;     // non-null: RMSNorm(x; gain, eps) is applied to x on the fly
+    float eps;
+    int32_t epi;
+    // EPI_RESID
+    const float* resid;    // [nb, N]
+    float* out;            // [nb, N]  (EPI_SWIGLU: [nb, N/2])
+    // EPI_QKV
+    float* q;              // [nb, hq*dh]
+    int32_t hq;
+    KvView kv;
+    const float2* rope;    // [max_seq_len, dh/2] (cos, sin)
+};
+void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st);
+
+struct DecodeAttn {
+    const float* q;        // [nb, hq*dh], already rotated
+    float* o;              // [nb, hq*dh]
+    int32_t nb, hq;
+    int32_t kv_dtype;
+    KvView kv;
+    int32_t nsplit;        // context splits per (sequence, head)
+    float* part_o;         // [nb*hq, nsplit, dh]
+    float* part_ml;        // [nb*hq, nsplit, 2]
+    int32_t* counters;     // [nb*hq], zero between launches
+};
+void launch_decode_attn(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st);
+
+// rows of x [M, d] fp32 -> RMSNorm -> out [M, d] in out_dtype
+void launch_rmsnorm(const float* x, const float* gain, float eps, void* out, int32_t out_dtype,
+                    int32_t M, int32_t d, hipStream_t st);
+
+// C = A W^T for many activation rows (prefill): A [M, K] and W [N, K] in dtype `dt`.
+struct PrefillGemm {
+    const void* A;
+    const void* W;
+    int32_t M, N, K;
+    int32_t dt;            // DType of A and W
+    int32_t epi;
+    int32_t T;             // tokens per sequence: row m is (sequence m / T, token m % T)
+    // EPI_RESID: fp32
+    const float* resid;    // [M, N]
+    float* out;            // [M, N]
+    // EPI_SWIGLU: out_act [M, N/2] in dtype dt
+    void* out_act;
+    // EPI_QKV
+    float* q;              // [M, hq*dh] fp32
+    int32_t hq;
+    KvView kv;
+    const float2* rope;
+};
+void launch_prefill_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st);
+
+struct PrefillAttn {
+    const float* q;        // [B*T, hq*dh] fp32, rotated
+    void* o;               // [B*T, hq*dh] in out_dtype
+    int32_t out_dtype;
+    int32_t B, T, hq;
+    int32_t kv_dtype;
+    KvView kv;
+};
+void launch_prefill_attn(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st);
+
+// block_table[idx[i]] = val[i] for i < n (n <= 128), stream-ordered.
+struct TableUpdate {
+    int32_t n;
+    int32_t idx[128];
+    int32_t val[128];
+};
+void launch_table_update(int32_t* table, const TableUpdate& u, hipStream_t st);
+
+}  // namespace shk

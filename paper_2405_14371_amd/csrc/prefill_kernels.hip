@@ -1,0 +1,396 @@
+// Prefill-phase kernels (EdgeShard Sec. 2: the whole prompt is consumed at once and fills
+// the KV cache).  The projections are dense contractions and run on the matrix cores
+// (MFMA) from LDS-staged tiles; attention runs QK^T and PV on the matrix cores with the
+// softmax statistics kept per lane and merged with one wavefront shuffle.
+#include "kernels.hpp"
+
+namespace shk {
+
+// ---------------------------------------------------------------------------------------
+// RMSNorm of rows: out = x * rsqrt(mean(x^2) + eps) * gain.  One workgroup per row.
+// ---------------------------------------------------------------------------------------
+template <typename OT>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
+                                                      float eps, OT* __restrict__ out, int d) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float* xr = x + static_cast<size_t>(blockIdx.x) * d;
+    OT* orow = out + static_cast<size_t>(blockIdx.x) * d;
+    float ssq = 0.f;
+    for (int c = tid * 4; c < d; c += 1024) {
+        const float4 t = *reinterpret_cast<const float4*>(xr + c);
+        ssq += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+    }
+    __shared__ float s_part[4];
+    ssq = wave_sum(ssq);
+    if (lane == 0) s_part[wave] = ssq;
+    __syncthreads();
+    const float tot = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
+    const float r = 1.0f / sqrtf(tot / static_cast<float>(d) + eps);
+    for (int c = tid * 4; c < d; c += 1024) {
+        const float4 t = *reinterpret_cast<const float4*>(xr + c);
+        const float4 g = *reinterpret_cast<const float4*>(gain + c);
+        orow[c] = Elem<OT>::from_f32(t.x * r * g.x);
+        orow[c + 1] = Elem<OT>::from_f32(t.y * r * g.y);
+        orow[c + 2] = Elem<OT>::from_f32(t.z * r * g.z);
+        orow[c + 3] = Elem<OT>::from_f32(t.w * r * g.w);
+    }
+}
+
+void launch_rmsnorm(const float* x, const float* gain, float eps, void* out, int32_t out_dtype,
+                    int32_t M, int32_t d, hipStream_t st) {
+    if (out_dtype == DT_F32)
+        hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(M), dim3(256), 0, st, x, gain, eps, static_cast<float*>(out), d);
+    else
+        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(M), dim3(256), 0, st, x, gain, eps, static_cast<bf16_t*>(out), d);
+}
+
+// ---------------------------------------------------------------------------------------
+// Shared epilogue of the prefill GEMMs.  The GEMMs compute the TRANSPOSED product
+// D[n][m] = sum_k W[n][k] A[m][k], so that in the 32x32 MFMA result layout a lane holds
+// one activation row m and four consecutive output features n..n+3: the element pairs
+// RoPE and SwiGLU work on sit in one lane, and results leave as 16-byte stores.
+// `val` = the four features n4..n4+3 (n4 % 4 == 0) of row m.
+// ---------------------------------------------------------------------------------------
+template <typename ET>
+__device__ __forceinline__ void gemm_epilogue(const PrefillGemm& a, const SeqBatch& sb, int m, int n4, const float val[4]) {
+    if (m >= a.M || n4 >= a.N) return;
+    if (a.epi == EPI_RESID) {
+        const size_t i = static_cast<size_t>(m) * a.N + n4;
+        const float4 r = *reinterpret_cast<const float4*>(a.resid + i);
+        float4 o;
+        o.x = r.x + val[0]; o.y = r.y + val[1]; o.z = r.z + val[2]; o.w = r.w + val[3];
+        *reinterpret_cast<float4*>(a.out + i) = o;
+        return;
+    }
+    if (a.epi == EPI_SWIGLU) {
+        const int F = a.N / 2;
+        ET* op = static_cast<ET*>(a.out_act) + static_cast<size_t>(m) * F + n4 / 2;
+        op[0] = Elem<ET>::from_f32(val[0] / (1.0f + expf(-val[0])) * val[1]);
+        op[1] = Elem<ET>::from_f32(val[2] / (1.0f + expf(-val[2])) * val[3]);
+        return;
+    }
+    // EPI_QKV
+    const int dh = a.kv.dh, nq = a.hq * dh, nk = a.kv.hkv * dh;
+    const int b = m / a.T, t = m % a.T;
+    const int pos = sb.pos[b] + t;
+    float r[4] = {val[0], val[1], val[2], val[3]};
+    const int e = n4 % dh;
+    if (n4 < nq + nk) {
+        const float2* cs = a.rope + static_cast<size_t>(pos) * (dh / 2) + e / 2;
+        const float2 c0 = cs[0], c1 = cs[1];
+        r[0] = val[0] * c0.x - val[1] * c0.y;
+        r[1] = val[0] * c0.y + val[1] * c0.x;
+        r[2] = val[2] * c1.x - val[3] * c1.y;
+        r[3] = val[2] * c1.y + val[3] * c1.x;
+    }
+    if (n4 < nq) {
+        float4 o; o.x = r[0]; o.y = r[1]; o.z = r[2]; o.w = r[3];
+        *reinterpret_cast<float4*>(a.q + static_cast<size_t>(m) * nq + n4) = o;
+        return;
+    }
+    const bool is_k = n4 < nq + nk;
+    const int hk = (n4 - nq - (is_k ? 0 : nk)) / dh;
+    const int page = a.kv.block_table[sb.seq[b] * a.kv.max_pages + pos / a.kv.page];
+    const size_t at = ((static_cast<size_t>(page) * a.kv.hkv + hk) * a.kv.page + pos % a.kv.page) * dh + e;
+    ET* dst = static_cast<ET*>(is_k ? a.kv.k : a.kv.v) + at;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) dst[i] = Elem<ET>::from_f32(r[i]);
+}
+
+// ---------------------------------------------------------------------------------------
+// GEMM on the matrix cores: v_mfma_f32_32x32x2_f32 for fp32 operands,
+// v_mfma_f32_32x32x16_bf16 for bf16 operands, fp32 accumulation in both.
+// Workgroup tile BN (features) x BM (rows), four waves in a 2x2 arrangement, each owning
+// (BN/2) x (BM/2) as 32x32 MFMA tiles.  K is walked in steps of 64 bytes per row (16 fp32
+// or 32 bf16) through two LDS stages: the global loads of step k+1 are in flight while
+// step k is multiplied.  LDS rows are k-contiguous with a pitch of 20 dwords, which makes
+// the 16-byte fragment reads conflict-free.  Within a 32-byte k group the lane with
+// half = lane/32 supplies the 16 bytes at offset 16*half - for fp32 that is a permutation
+// of k (the same on both operands, so the sum over k is unchanged), for bf16 it is the
+// instruction's native operand layout.
+// ---------------------------------------------------------------------------------------
+constexpr int GEMM_ROW_DW = 16;   // dwords of k per row per step
+constexpr int GEMM_PITCH = 20;    // LDS row pitch in dwords
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+
+template <typename T>
+__device__ __forceinline__ void mfma_chunk(const float4& w, const float4& x, f32x16& acc);
+template <>
+__device__ __forceinline__ void mfma_chunk<float>(const float4& w, const float4& x, f32x16& acc) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.x, x.x, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.y, x.y, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.z, x.z, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.w, x.w, acc, 0, 0, 0);
+}
+template <>
+__device__ __forceinline__ void mfma_chunk<bf16_t>(const float4& w, const float4& x, f32x16& acc) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, w), __builtin_bit_cast(bf16x8_t, x),
+                                                  acc, 0, 0, 0);
+}
+
+template <typename T, int BN, int BM>
+__global__ __launch_bounds__(256) void gemm_kernel(PrefillGemm a, SeqBatch sb, int tiles_m, int tiles_total) {
+    constexpr int VEC = Elem<T>::VEC;          // elements per 16 bytes
+    constexpr int BK = GEMM_ROW_DW / 4 * VEC;  // elements of k per step
+    constexpr int TN = BN / 64, TM = BM / 64;  // MFMA tiles per wave
+    constexpr int LW = BN * 4 / 256, LX = BM * 4 / 256;  // 16-byte loads per thread per stage
+    __shared__ __attribute__((aligned(16))) float sW[2][BN * GEMM_PITCH];
+    __shared__ __attribute__((aligned(16))) float sX[2][BM * GEMM_PITCH];
+
+    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
+    // tiles so that the workgroups sharing a W tile also share an L2.
+    const int per_xcd = (tiles_total + 7) / 8;
+    const int tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (tile >= tiles_total) return;
+    const int n0 = (tile / tiles_m) * BN, m0 = (tile % tiles_m) * BM;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wn = wave >> 1, wm = wave & 1;
+    const int l32 = lane & 31, half = lane >> 5;
+    const T* __restrict__ W = static_cast<const T*>(a.W);
+    const T* __restrict__ X = static_cast<const T*>(a.A);
+
+    f32x16 acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    float4 gw[LW], gx[LX];
+    auto gload = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < LW; ++i) {
+            const int idx = tid + 256 * i, row = idx >> 2, k = k0 + (idx & 3) * VEC;
+            const bool ok = (n0 + row < a.N) && (k < a.K);
+            gw[i] = ok ? *reinterpret_cast<const float4*>(W + static_cast<size_t>(n0 + row) * a.K + k)
+                       : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int i = 0; i < LX; ++i) {
+            const int idx = tid + 256 * i, row = idx >> 2, k = k0 + (idx & 3) * VEC;
+            const bool ok = (m0 + row < a.M) && (k < a.K);
+            gx[i] = ok ? *reinterpret_cast<const float4*>(X + static_cast<size_t>(m0 + row) * a.K + k)
+                       : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    auto sstore = [&](int stage) {
+#pragma unroll
+        for (int i = 0; i < LW; ++i) {
+            const int idx = tid + 256 * i;
+            *reinterpret_cast<float4*>(&sW[stage][(idx >> 2) * GEMM_PITCH + (idx & 3) * 4]) = gw[i];
+        }
+#pragma unroll
+        for (int i = 0; i < LX; ++i) {
+            const int idx = tid + 256 * i;
+            *reinterpret_cast<float4*>(&sX[stage][(idx >> 2) * GEMM_PITCH + (idx & 3) * 4]) = gx[i];
+        }
+    };
+
+    const int ksteps = (a.K + BK - 1) / BK;
+    gload(0);
+    sstore(0);
+    __syncthreads();
+    for (int ks = 0; ks < ksteps; ++ks) {
+        const int stage = ks & 1;
+        if (ks + 1 < ksteps) gload((ks + 1) * BK);
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            float4 fw[TN], fx[TM];
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+                fw[i] = *reinterpret_cast<const float4*>(
+                    &sW[stage][(wn * (BN / 2) + i * 32 + l32) * GEMM_PITCH + kk * 8 + half * 4]);
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+                fx[j] = *reinterpret_cast<const float4*>(
+                    &sX[stage][(wm * (BM / 2) + j * 32 + l32) * GEMM_PITCH + kk * 8 + half * 4]);
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int j = 0; j < TM; ++j) mfma_chunk<T>(fw[i], fx[j], acc[i][j]);
+        }
+        if (ks + 1 < ksteps) sstore(stage ^ 1);
+        __syncthreads();
+    }
+
+    // D[n][m]: register v of a lane is feature 8*(v/4) + 4*half + v%4, row l32 of its tile.
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const int n4 = n0 + wn * (BN / 2) + i * 32 + vq * 8 + half * 4;
+                const int m = m0 + wm * (BM / 2) + j * 32 + l32;
+                const float val[4] = {acc[i][j][vq * 4], acc[i][j][vq * 4 + 1], acc[i][j][vq * 4 + 2], acc[i][j][vq * 4 + 3]};
+                gemm_epilogue<T>(a, sb, m, n4, val);
+            }
+}
+
+template <typename T, int BN, int BM>
+static void launch_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
+    const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+    const int total = tiles_m * tiles_n;
+    const int grid = ((total + 7) / 8) * 8;
+    hipLaunchKernelGGL((gemm_kernel<T, BN, BM>), dim3(grid), dim3(256), 0, st, a, sb, tiles_m, total);
+}
+
+template <typename T>
+static void launch_gemm_t(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
+    // the larger tile only when it still gives every compute unit two workgroups
+    const long t128 = static_cast<long>((a.M + 127) / 128) * ((a.N + 127) / 128);
+    if (t128 >= 512) launch_gemm<T, 128, 128>(a, sb, st);
+    else launch_gemm<T, 128, 64>(a, sb, st);
+}
+
+void launch_prefill_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
+    if (a.dt == DT_F32) launch_gemm_t<float>(a, sb, st);
+    else launch_gemm_t<bf16_t>(a, sb, st);
+}
+
+// ---------------------------------------------------------------------------------------
+// Causal attention for the T new tokens of each sequence over its cache (positions
+// 0 .. P+T-1).  One wave owns 32 query rows of one head; the four waves of a workgroup
+// take four heads of the same query tile, so they carry equal work.  Per 32-key tile:
+//   S^T[key][q] = sum_d K[key][d] Q[q][d]      (MFMA, K and Q fragments k-contiguous)
+//   a lane then holds 16 keys of ONE query column: row max / row sum are in-lane
+//   reductions plus a single shuffle with lane^32;
+//   O^T[d][q] += sum_key V[key][d] P^T[key][q]  (MFMA; P^T is already in B-operand layout).
+// ---------------------------------------------------------------------------------------
+template <typename KT>
+__device__ __forceinline__ float4 load4(const KT* p);
+template <>
+__device__ __forceinline__ float4 load4<float>(const float* p) { return *reinterpret_cast<const float4*>(p); }
+template <>
+__device__ __forceinline__ float4 load4<bf16_t>(const bf16_t* p) {
+    const uint2 t = *reinterpret_cast<const uint2*>(p);
+    return make_float4(__uint_as_float(t.x << 16), __uint_as_float(t.x & 0xFFFF0000u),
+                       __uint_as_float(t.y << 16), __uint_as_float(t.y & 0xFFFF0000u));
+}
+
+template <typename KT, typename OT, int DH>
+__global__ __launch_bounds__(256) void prefill_attn_kernel(PrefillAttn a, SeqBatch sb) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int qt = gridDim.x - 1 - blockIdx.x;  // longest rows first
+    const int h = blockIdx.y * 4 + wave;
+    const int b = blockIdx.z;
+    if (h >= a.hq) return;
+    const int hk = h / (a.hq / a.kv.hkv);
+    const int P = sb.pos[b];
+    const int32_t* bt = a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages;
+    const KT* __restrict__ kp = static_cast<const KT*>(a.kv.k);
+    const KT* __restrict__ vp = static_cast<const KT*>(a.kv.v);
+    const int ctx = P + a.T;
+    const int page = a.kv.page, hkv = a.kv.hkv;
+
+    const int t_q = qt * 32 + l32;                // this lane's query row within the call
+    const int t_ld = min(t_q, a.T - 1);
+    const size_t qrow = (static_cast<size_t>(b) * a.T + t_ld) * a.hq * DH + h * DH;
+    const float scale = 1.0f / sqrtf(static_cast<float>(DH));
+    float4 qf[DH / 8];
+#pragma unroll
+    for (int j = 0; j < DH / 8; ++j) {
+        qf[j] = *reinterpret_cast<const float4*>(a.q + qrow + j * 8 + half * 4);
+        qf[j].x *= scale; qf[j].y *= scale; qf[j].z *= scale; qf[j].w *= scale;
+    }
+    f32x16 o[DH / 32];
+#pragma unroll
+    for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[j][v] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+    const int pos_q = P + t_q;
+    const int last_key = P + min(qt * 32 + 31, a.T - 1);
+
+    for (int k0 = 0; k0 <= last_key; k0 += 32) {
+        // S^T tile
+        const int u = min(k0 + l32, ctx - 1);
+        const size_t kat = ((static_cast<size_t>(bt[u / page]) * hkv + hk) * page + u % page) * DH + half * 4;
+        f32x16 s;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[v] = 0.f;
+#pragma unroll
+        for (int j = 0; j < DH / 8; ++j) {
+            const float4 kf = load4<KT>(kp + kat + j * 8);
+            s = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.x, qf[j].x, s, 0, 0, 0);
+            s = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.y, qf[j].y, s, 0, 0, 0);
+            s = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.z, qf[j].z, s, 0, 0, 0);
+            s = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.w, qf[j].w, s, 0, 0, 0);
+        }
+        // causal mask + running softmax for this lane's query column
+        float mx = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int key = k0 + (v >> 2) * 8 + half * 4 + (v & 3);
+            if (key > pos_q) s[v] = -INFINITY;
+            mx = fmaxf(mx, s[v]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        // rows beyond T (t_q >= T) can be fully masked in a tile; keep them finite
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float corr = __expf(m_run - m_use);
+        float rs = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            s[v] = __expf(s[v] - m_use);
+            rs += s[v];
+        }
+        rs += __shfl_xor(rs, 32, 64);
+        l_run = l_run * corr + rs;
+        m_run = m_new;
+#pragma unroll
+        for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[j][v] *= corr;
+        // O^T += V^T P^T
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int key = min(k0 + (v >> 2) * 8 + half * 4 + (v & 3), ctx - 1);
+            const size_t vat = ((static_cast<size_t>(bt[key / page]) * hkv + hk) * page + key % page) * DH + l32;
+#pragma unroll
+            for (int j = 0; j < DH / 32; ++j) {
+                const float vv = Elem<KT>::to_f32(vp[vat + j * 32]);
+                o[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(vv, s[v], o[j], 0, 0, 0);
+            }
+        }
+    }
+
+    if (t_q >= a.T) return;
+    const float inv = 1.0f / l_run;
+    OT* op = static_cast<OT*>(a.o) + (static_cast<size_t>(b) * a.T + t_q) * a.hq * DH + h * DH;
+#pragma unroll
+    for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+            const int d = j * 32 + vq * 8 + half * 4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) op[d + i] = Elem<OT>::from_f32(o[j][vq * 4 + i] * inv);
+        }
+}
+
+template <typename KT, typename OT>
+static void launch_pa(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st) {
+    const dim3 grid((a.T + 31) / 32, (a.hq + 3) / 4, a.B), block(256);
+    switch (a.kv.dh) {
+        case 32: hipLaunchKernelGGL((prefill_attn_kernel<KT, OT, 32>), grid, block, 0, st, a, sb); break;
+        case 64: hipLaunchKernelGGL((prefill_attn_kernel<KT, OT, 64>), grid, block, 0, st, a, sb); break;
+        default: hipLaunchKernelGGL((prefill_attn_kernel<KT, OT, 128>), grid, block, 0, st, a, sb); break;
+    }
+}
+
+void launch_prefill_attn(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st) {
+    if (a.kv_dtype == DT_F32) {
+        if (a.out_dtype == DT_F32) launch_pa<float, float>(a, sb, st);
+        else launch_pa<float, bf16_t>(a, sb, st);
+    } else {
+        if (a.out_dtype == DT_F32) launch_pa<bf16_t, float>(a, sb, st);
+        else launch_pa<bf16_t, bf16_t>(a, sb, st);
+    }
+}
+
+}  // namespace shk

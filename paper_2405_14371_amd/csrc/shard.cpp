@@ -1,0 +1,630 @@
+// Shard runtime and C-ABI (see include/shard.h): weight packing, the pre-allocated paged
+// KV pool, per-call validation, and the per-layer launch sequence for the prefill and the
+// autoregressive phase.  All arithmetic of the layer happens in the kernels; this file
+// only moves pointers.
+#include "../../include/shard.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "kernels.hpp"
+
+using namespace shk;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                         \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess)                                                                 \
+            return fail(e_ == hipErrorOutOfMemory ? SHARD_E_NOMEM : SHARD_E_HIP, "%s: %s", #expr, \
+                        hipGetErrorString(e_));                                               \
+    } while (0)
+
+struct LayerDev {
+    void* wqkv = nullptr;  // [(Hq+2Hkv)*dh, d]   rows: all q heads, all k heads, all v heads
+    void* wo = nullptr;    // [d, Hq*dh]
+    void* wgu = nullptr;   // [2F, d]             row 2f = gate_f, row 2f+1 = up_f
+    void* wd = nullptr;    // [d, F]
+    float* g_attn = nullptr;
+    float* g_ffn = nullptr;
+    void* k = nullptr;     // [n_pages, Hkv, page, dh]
+    void* v = nullptr;
+};
+
+struct Timing {
+    bool on = false;
+    std::vector<hipEvent_t> ev[SHARD_K_COUNT];  // start, stop, start, stop, ...
+    size_t used[SHARD_K_COUNT] = {0};
+    int64_t launches[SHARD_K_COUNT] = {0};
+    double seconds[SHARD_K_COUNT] = {0};
+    hipStream_t last_stream = nullptr;
+};
+
+}  // namespace
+
+struct shard {
+    shard_model_cfg m{};
+    shard_kv_cfg kv{};
+    int layer_lo = 0, layer_hi = 0, L = 0;
+    int es = 4;           // bytes per weight / cache element
+    int nqkv = 0, nq = 0;
+    int max_pages = 0, n_pages = 0, mmax = 0;
+    std::vector<LayerDev> layers;
+    float2* rope = nullptr;          // [max_seq_len, dh/2]
+    int32_t* block_table = nullptr;  // device [max_seqs, max_pages]
+    std::vector<int32_t> free_pages; // stack
+    std::vector<int32_t> seq_len;    // -1 = slot not live
+    std::vector<int32_t> seq_pages;  // pages held per slot
+    std::vector<int32_t> host_table; // mirror of block_table
+    // workspace
+    void* h = nullptr;     // [mmax, d]      normalised activations (weight dtype)
+    float* q = nullptr;    // [mmax, Hq*dh]
+    void* o = nullptr;     // [mmax, Hq*dh]  attention output (fp32 in decode, weight dtype in prefill)
+    void* f = nullptr;     // [mmax, F]      SwiGLU output   (same)
+    float* part_o = nullptr;
+    float* part_ml = nullptr;
+    int32_t* counters = nullptr;
+    int nsplit_max = 32;
+    Timing timing;
+    std::vector<hipEvent_t> layer_ev;  // L+1 events, used by shard_profile
+    bool record_layers = false;
+};
+
+namespace {
+
+void free_all(shard* s) {
+    for (auto& l : s->layers) {
+        void* ptrs[] = {l.wqkv, l.wo, l.wgu, l.wd, l.g_attn, l.g_ffn, l.k, l.v};
+        for (void* p : ptrs)
+            if (p) (void)hipFree(p);
+    }
+    void* ptrs[] = {s->rope, s->block_table, s->h, s->q, s->o, s->f, s->part_o, s->part_ml, s->counters};
+    for (void* p : ptrs)
+        if (p) (void)hipFree(p);
+    for (auto& v : s->timing.ev)
+        for (hipEvent_t e : v) (void)hipEventDestroy(e);
+    for (hipEvent_t e : s->layer_ev) (void)hipEventDestroy(e);
+    delete s;
+}
+
+int validate_cfg(const shard_model_cfg* m, const shard_kv_cfg* kv, int lo, int hi) {
+    if (!m || !kv) return fail(SHARD_E_INVAL, "null configuration");
+    if (lo < 0 || hi <= lo) return fail(SHARD_E_INVAL, "layer range [%d,%d) is empty or negative", lo, hi);
+    if (m->d_model <= 0 || m->n_heads <= 0 || m->n_kv_heads <= 0 || m->ffn_dim <= 0)
+        return fail(SHARD_E_INVAL, "model dimensions must be positive");
+    if (m->head_dim != 32 && m->head_dim != 64 && m->head_dim != 128)
+        return fail(SHARD_E_INVAL, "head_dim %d unsupported (32, 64, 128)", m->head_dim);
+    if (m->n_heads % m->n_kv_heads) return fail(SHARD_E_INVAL, "n_heads %% n_kv_heads != 0");
+    if (m->d_model % 8 || m->ffn_dim % 8)
+        return fail(SHARD_E_INVAL, "d_model and ffn_dim must be multiples of 8 (16-byte rows)");
+    if (m->weight_dtype != SHARD_F32 && m->weight_dtype != SHARD_BF16)
+        return fail(SHARD_E_INVAL, "unknown weight_dtype %d", m->weight_dtype);
+    if (m->act_dtype != SHARD_F32) return fail(SHARD_E_INVAL, "act_dtype must be SHARD_F32");
+    if (!(m->rms_eps >= 0.f) || !(m->rope_theta > 0.f)) return fail(SHARD_E_INVAL, "bad rms_eps / rope_theta");
+    if (kv->max_seqs < 1 || kv->max_seq_len < 1 || kv->page_size < 1 || kv->max_batch_tokens < 0)
+        return fail(SHARD_E_INVAL, "bad KV configuration");
+    return SHARD_OK;
+}
+
+// start/stop event pair around one launch when timing is enabled
+struct Bracket {
+    shard* s;
+    int klass;
+    hipStream_t st;
+    hipEvent_t stop = nullptr;
+    Bracket(shard* s_, int klass_, hipStream_t st_) : s(s_), klass(klass_), st(st_) {
+        Timing& t = s->timing;
+        if (!t.on) return;
+        auto& v = t.ev[klass];
+        if (t.used[klass] + 2 > v.size()) {
+            if (v.size() >= (1u << 16)) return;  // bounded; further launches go untimed
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess) return;
+            if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+            v.push_back(a);
+            v.push_back(b);
+        }
+        (void)hipEventRecord(v[t.used[klass]], st);
+        stop = v[t.used[klass] + 1];
+        t.used[klass] += 2;
+        t.last_stream = st;
+    }
+    ~Bracket() {
+        if (stop) (void)hipEventRecord(stop, st);
+    }
+};
+
+KvView kv_view(const shard* s, int li) {
+    KvView v;
+    v.k = s->layers[li].k;
+    v.v = s->layers[li].v;
+    v.block_table = s->block_table;
+    v.max_pages = s->max_pages;
+    v.page = s->kv.page_size;
+    v.hkv = s->m.n_kv_heads;
+    v.dh = s->m.head_dim;
+    return v;
+}
+
+// Reserve pages so that every sequence of the batch can hold `add` more tokens, and
+// enqueue the block-table writes.  Cannot fail: the pool holds max_pages per sequence.
+void grow_sequences(shard* s, const SeqBatch& sb, int add, hipStream_t st) {
+    TableUpdate u;
+    u.n = 0;
+    for (int b = 0; b < sb.n; ++b) {
+        const int seq = sb.seq[b];
+        const int need = (sb.pos[b] + add + s->kv.page_size - 1) / s->kv.page_size;
+        while (s->seq_pages[seq] < need) {
+            const int32_t page = s->free_pages.back();
+            s->free_pages.pop_back();
+            const int idx = seq * s->max_pages + s->seq_pages[seq]++;
+            s->host_table[idx] = page;
+            u.idx[u.n] = idx;
+            u.val[u.n] = page;
+            if (++u.n == 128) {
+                launch_table_update(s->block_table, u, st);
+                u.n = 0;
+            }
+        }
+    }
+    if (u.n) launch_table_update(s->block_table, u, st);
+}
+
+int check_batch(shard* s, const int32_t* seq_ids, int B, int T, bool decode, SeqBatch* sb) {
+    if (!s) return fail(SHARD_E_INVAL, "null shard");
+    if (!seq_ids) return fail(SHARD_E_INVAL, "null seq_ids");
+    if (B < 1 || B > SHARD_MAX_BATCH) return fail(SHARD_E_INVAL, "B=%d outside 1..%d", B, SHARD_MAX_BATCH);
+    if (T < 1) return fail(SHARD_E_INVAL, "T=%d < 1", T);
+    if (static_cast<long>(B) * T > s->mmax)
+        return fail(SHARD_E_INVAL, "B*T=%ld exceeds max_batch_tokens=%d", static_cast<long>(B) * T, s->mmax);
+    sb->n = B;
+    for (int b = 0; b < B; ++b) {
+        const int id = seq_ids[b];
+        if (id < 0 || id >= s->kv.max_seqs || s->seq_len[id] < 0)
+            return fail(SHARD_E_STATE, "seq_id %d is not live", id);
+        for (int c = 0; c < b; ++c)
+            if (seq_ids[c] == id) return fail(SHARD_E_STATE, "seq_id %d appears twice in the batch", id);
+        if (decode && s->seq_len[id] == 0) return fail(SHARD_E_STATE, "decode on empty sequence %d", id);
+        if (s->seq_len[id] + T > s->kv.max_seq_len)
+            return fail(SHARD_E_KV_FULL, "sequence %d: %d cached + %d new > max_seq_len %d", id, s->seq_len[id], T,
+                        s->kv.max_seq_len);
+        sb->seq[b] = id;
+        sb->pos[b] = s->seq_len[id];
+    }
+    return SHARD_OK;
+}
+
+void mark_layer(shard* s, int i, hipStream_t st) {
+    if (s->record_layers) (void)hipEventRecord(s->layer_ev[i], st);
+}
+
+void run_prefill(shard* s, const SeqBatch& sb, int T, const float* x_in, float* x_out, hipStream_t st) {
+    const shard_model_cfg& m = s->m;
+    const int M = sb.n * T;
+    const int dt = m.weight_dtype == SHARD_F32 ? DT_F32 : DT_BF16;
+    mark_layer(s, 0, st);
+    for (int li = 0; li < s->L; ++li) {
+        const LayerDev& l = s->layers[li];
+        const float* x = li == 0 ? x_in : x_out;
+        {
+            Bracket t(s, SHARD_K_OTHER, st);
+            launch_rmsnorm(x, l.g_attn, m.rms_eps, s->h, dt, M, m.d_model, st);
+        }
+        PrefillGemm g{};
+        g.M = M; g.dt = dt; g.T = T; g.hq = m.n_heads; g.kv = kv_view(s, li); g.rope = s->rope;
+        g.A = s->h; g.W = l.wqkv; g.N = s->nqkv; g.K = m.d_model; g.epi = EPI_QKV; g.q = s->q;
+        {
+            Bracket t(s, SHARD_K_PREFILL_GEMM, st);
+            launch_prefill_gemm(g, sb, st);
+        }
+        PrefillAttn at{};
+        at.q = s->q; at.o = s->o; at.out_dtype = dt; at.B = sb.n; at.T = T; at.hq = m.n_heads;
+        at.kv_dtype = dt; at.kv = g.kv;
+        {
+            Bracket t(s, SHARD_K_PREFILL_ATTN, st);
+            launch_prefill_attn(at, sb, st);
+        }
+        g.A = s->o; g.W = l.wo; g.N = m.d_model; g.K = s->nq; g.epi = EPI_RESID; g.resid = x; g.out = x_out;
+        {
+            Bracket t(s, SHARD_K_PREFILL_GEMM, st);
+            launch_prefill_gemm(g, sb, st);
+        }
+        {
+            Bracket t(s, SHARD_K_OTHER, st);
+            launch_rmsnorm(x_out, l.g_ffn, m.rms_eps, s->h, dt, M, m.d_model, st);
+        }
+        g.A = s->h; g.W = l.wgu; g.N = 2 * m.ffn_dim; g.K = m.d_model; g.epi = EPI_SWIGLU; g.out_act = s->f;
+        {
+            Bracket t(s, SHARD_K_PREFILL_GEMM, st);
+            launch_prefill_gemm(g, sb, st);
+        }
+        g.A = s->f; g.W = l.wd; g.N = m.d_model; g.K = m.ffn_dim; g.epi = EPI_RESID; g.resid = x_out; g.out = x_out;
+        {
+            Bracket t(s, SHARD_K_PREFILL_GEMM, st);
+            launch_prefill_gemm(g, sb, st);
+        }
+        mark_layer(s, li + 1, st);
+    }
+}
+
+int pick_nsplit(const shard* s, const SeqBatch& sb) {
+    int ctx = 1;
+    for (int b = 0; b < sb.n; ++b) ctx = ctx > sb.pos[b] + 1 ? ctx : sb.pos[b] + 1;
+    const int units = sb.n * s->m.n_heads;
+    int n = (1024 + units - 1) / units;            // aim at ~4 workgroups per compute unit
+    const int by_len = (ctx + 31) / 32;             // at least 32 tokens per slice
+    if (n > by_len) n = by_len;
+    if (n > s->nsplit_max) n = s->nsplit_max;
+    return n < 1 ? 1 : n;
+}
+
+void run_decode(shard* s, const SeqBatch& sb, const float* x_in, float* x_out, hipStream_t st) {
+    const shard_model_cfg& m = s->m;
+    const int dt = m.weight_dtype == SHARD_F32 ? DT_F32 : DT_BF16;
+    const int B = sb.n;
+    float* o = static_cast<float*>(s->o);
+    float* f = static_cast<float*>(s->f);
+    mark_layer(s, 0, st);
+    for (int li = 0; li < s->L; ++li) {
+        const LayerDev& l = s->layers[li];
+        const float* x = li == 0 ? x_in : x_out;
+        const KvView kvv = kv_view(s, li);
+        // the streaming kernels take up to 8 activation rows per pass over the weights
+        for (int b0 = 0; b0 < B; b0 += 8) {
+            const int nb = B - b0 < 8 ? B - b0 : 8;
+            SeqBatch sub;
+            sub.n = nb;
+            for (int i = 0; i < nb; ++i) { sub.seq[i] = sb.seq[b0 + i]; sub.pos[i] = sb.pos[b0 + i]; }
+            DecodeLinear d{};
+            d.W = l.wqkv; d.N = s->nqkv; d.K = m.d_model; d.wt = dt; d.nb = nb;
+            d.x = x + static_cast<size_t>(b0) * m.d_model; d.gain = l.g_attn; d.eps = m.rms_eps;
+            d.epi = EPI_QKV; d.q = s->q + static_cast<size_t>(b0) * s->nq; d.hq = m.n_heads; d.kv = kvv; d.rope = s->rope;
+            Bracket t(s, SHARD_K_DECODE_LINEAR, st);
+            launch_decode_linear(d, sub, st);
+        }
+        {
+            DecodeAttn a{};
+            a.q = s->q; a.o = o; a.nb = B; a.hq = m.n_heads; a.kv_dtype = dt; a.kv = kvv;
+            a.nsplit = pick_nsplit(s, sb); a.part_o = s->part_o; a.part_ml = s->part_ml; a.counters = s->counters;
+            Bracket t(s, SHARD_K_DECODE_ATTN, st);
+            launch_decode_attn(a, sb, st);
+        }
+        for (int b0 = 0; b0 < B; b0 += 8) {
+            const int nb = B - b0 < 8 ? B - b0 : 8;
+            DecodeLinear d{};
+            d.W = l.wo; d.N = m.d_model; d.K = s->nq; d.wt = dt; d.nb = nb;
+            d.x = o + static_cast<size_t>(b0) * s->nq; d.epi = EPI_RESID;
+            d.resid = x + static_cast<size_t>(b0) * m.d_model; d.out = x_out + static_cast<size_t>(b0) * m.d_model;
+            Bracket t(s, SHARD_K_DECODE_LINEAR, st);
+            launch_decode_linear(d, sb, st);
+        }
+        for (int b0 = 0; b0 < B; b0 += 8) {
+            const int nb = B - b0 < 8 ? B - b0 : 8;
+            DecodeLinear d{};
+            d.W = l.wgu; d.N = 2 * m.ffn_dim; d.K = m.d_model; d.wt = dt; d.nb = nb;
+            d.x = x_out + static_cast<size_t>(b0) * m.d_model; d.gain = l.g_ffn; d.eps = m.rms_eps;
+            d.epi = EPI_SWIGLU; d.out = f + static_cast<size_t>(b0) * m.ffn_dim;
+            Bracket t(s, SHARD_K_DECODE_LINEAR, st);
+            launch_decode_linear(d, sb, st);
+        }
+        for (int b0 = 0; b0 < B; b0 += 8) {
+            const int nb = B - b0 < 8 ? B - b0 : 8;
+            DecodeLinear d{};
+            d.W = l.wd; d.N = m.d_model; d.K = m.ffn_dim; d.wt = dt; d.nb = nb;
+            d.x = f + static_cast<size_t>(b0) * m.ffn_dim; d.epi = EPI_RESID;
+            d.resid = x_out + static_cast<size_t>(b0) * m.d_model; d.out = x_out + static_cast<size_t>(b0) * m.d_model;
+            Bracket t(s, SHARD_K_DECODE_LINEAR, st);
+            launch_decode_linear(d, sb, st);
+        }
+        mark_layer(s, li + 1, st);
+    }
+}
+
+int check_launch() {
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(SHARD_E_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+    return SHARD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* shard_last_error(void) { return g_err.c_str(); }
+
+int shard_create(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg* kv, int32_t layer_lo,
+                 int32_t layer_hi, const shard_layer_weights* w, int32_t weights_on_device) {
+    if (!out) return fail(SHARD_E_INVAL, "null out");
+    *out = nullptr;
+    int rc = validate_cfg(model, kv, layer_lo, layer_hi);
+    if (rc) return rc;
+    if (!w) return fail(SHARD_E_INVAL, "null weights");
+    const int L = layer_hi - layer_lo;
+    for (int i = 0; i < L; ++i) {
+        const void* ptrs[] = {w[i].wq, w[i].wk, w[i].wv, w[i].wo, w[i].w_gate, w[i].w_up, w[i].w_down, w[i].g_attn, w[i].g_ffn};
+        for (const void* p : ptrs)
+            if (!p) return fail(SHARD_E_INVAL, "layer %d has a null tensor", layer_lo + i);
+    }
+    shard* s = new (std::nothrow) shard();
+    if (!s) return fail(SHARD_E_NOMEM, "host allocation failed");
+    s->m = *model;
+    s->kv = *kv;
+    s->layer_lo = layer_lo; s->layer_hi = layer_hi; s->L = L;
+    s->es = model->weight_dtype == SHARD_F32 ? 4 : 2;
+    const int d = model->d_model, dh = model->head_dim, F = model->ffn_dim;
+    s->nq = model->n_heads * dh;
+    const int nkv = model->n_kv_heads * dh;
+    s->nqkv = s->nq + 2 * nkv;
+    s->max_pages = (kv->max_seq_len + kv->page_size - 1) / kv->page_size;
+    s->n_pages = s->max_pages * kv->max_seqs;
+    s->mmax = kv->max_batch_tokens > 0 ? kv->max_batch_tokens : kv->max_seq_len;
+    if (s->mmax < SHARD_MAX_BATCH) s->mmax = SHARD_MAX_BATCH;  // decode batches
+    s->layers.resize(L);
+
+    const size_t es = s->es;
+    const hipMemcpyKind kind = weights_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+#define CREATE_TRY(expr)                                                                      \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess) {                                                               \
+            free_all(s);                                                                      \
+            return fail(e_ == hipErrorOutOfMemory ? SHARD_E_NOMEM : SHARD_E_HIP, "%s: %s", #expr, \
+                        hipGetErrorString(e_));                                               \
+        }                                                                                     \
+    } while (0)
+
+    const size_t page_elems = static_cast<size_t>(model->n_kv_heads) * kv->page_size * dh;
+    for (int i = 0; i < L; ++i) {
+        LayerDev& l = s->layers[i];
+        CREATE_TRY(hipMalloc(&l.wqkv, static_cast<size_t>(s->nqkv) * d * es));
+        CREATE_TRY(hipMalloc(&l.wo, static_cast<size_t>(d) * s->nq * es));
+        CREATE_TRY(hipMalloc(&l.wgu, static_cast<size_t>(2) * F * d * es));
+        CREATE_TRY(hipMalloc(&l.wd, static_cast<size_t>(d) * F * es));
+        CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&l.g_attn), d * sizeof(float)));
+        CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&l.g_ffn), d * sizeof(float)));
+        CREATE_TRY(hipMalloc(&l.k, page_elems * s->n_pages * es));
+        CREATE_TRY(hipMalloc(&l.v, page_elems * s->n_pages * es));
+        char* qkv = static_cast<char*>(l.wqkv);
+        CREATE_TRY(hipMemcpy(qkv, w[i].wq, static_cast<size_t>(s->nq) * d * es, kind));
+        CREATE_TRY(hipMemcpy(qkv + static_cast<size_t>(s->nq) * d * es, w[i].wk, static_cast<size_t>(nkv) * d * es, kind));
+        CREATE_TRY(hipMemcpy(qkv + static_cast<size_t>(s->nq + nkv) * d * es, w[i].wv, static_cast<size_t>(nkv) * d * es, kind));
+        CREATE_TRY(hipMemcpy(l.wo, w[i].wo, static_cast<size_t>(d) * s->nq * es, kind));
+        // gate and up rows interleaved: a 2-D copy with twice the destination pitch
+        const size_t rowb = static_cast<size_t>(d) * es;
+        CREATE_TRY(hipMemcpy2D(l.wgu, 2 * rowb, w[i].w_gate, rowb, rowb, F, kind));
+        CREATE_TRY(hipMemcpy2D(static_cast<char*>(l.wgu) + rowb, 2 * rowb, w[i].w_up, rowb, rowb, F, kind));
+        CREATE_TRY(hipMemcpy(l.wd, w[i].w_down, static_cast<size_t>(d) * F * es, kind));
+        CREATE_TRY(hipMemcpy(l.g_attn, w[i].g_attn, d * sizeof(float), kind));
+        CREATE_TRY(hipMemcpy(l.g_ffn, w[i].g_ffn, d * sizeof(float), kind));
+        // a cache that was never written must still hold finite numbers (masked lanes read it)
+        CREATE_TRY(hipMemset(l.k, 0, page_elems * s->n_pages * es));
+        CREATE_TRY(hipMemset(l.v, 0, page_elems * s->n_pages * es));
+    }
+
+    // cos/sin of pos * theta^(-2i/dh), evaluated in double on the host and rounded once
+    {
+        std::vector<float2> tab(static_cast<size_t>(kv->max_seq_len) * (dh / 2));
+        for (int p = 0; p < kv->max_seq_len; ++p)
+            for (int i = 0; i < dh / 2; ++i) {
+                const double ang = p * std::pow(static_cast<double>(model->rope_theta), -2.0 * i / dh);
+                tab[static_cast<size_t>(p) * (dh / 2) + i] = make_float2(static_cast<float>(std::cos(ang)),
+                                                                         static_cast<float>(std::sin(ang)));
+            }
+        CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&s->rope), tab.size() * sizeof(float2)));
+        CREATE_TRY(hipMemcpy(s->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice));
+    }
+
+    const size_t bt_elems = static_cast<size_t>(kv->max_seqs) * s->max_pages;
+    CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&s->block_table), bt_elems * sizeof(int32_t)));
+    CREATE_TRY(hipMemset(s->block_table, 0, bt_elems * sizeof(int32_t)));
+    s->host_table.assign(bt_elems, 0);
+    s->free_pages.resize(s->n_pages);
+    for (int i = 0; i < s->n_pages; ++i) s->free_pages[i] = i;  // popped from the back: highest page first
+    s->seq_len.assign(kv->max_seqs, -1);
+    s->seq_pages.assign(kv->max_seqs, 0);
+
+    const size_t mm = s->mmax;
+    CREATE_TRY(hipMalloc(&s->h, mm * d * es));
+    CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&s->q), mm * s->nq * sizeof(float)));
+    CREATE_TRY(hipMalloc(&s->o, mm * s->nq * sizeof(float)));
+    CREATE_TRY(hipMalloc(&s->f, mm * F * sizeof(float)));
+    const size_t units = static_cast<size_t>(SHARD_MAX_BATCH) * model->n_heads;
+    CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&s->part_o), units * s->nsplit_max * dh * sizeof(float)));
+    CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&s->part_ml), units * s->nsplit_max * 2 * sizeof(float)));
+    CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&s->counters), units * sizeof(int32_t)));
+    CREATE_TRY(hipMemset(s->counters, 0, units * sizeof(int32_t)));
+    s->layer_ev.resize(L + 1);
+    for (auto& e : s->layer_ev) e = nullptr;
+    for (auto& e : s->layer_ev) CREATE_TRY(hipEventCreate(&e));
+    CREATE_TRY(hipDeviceSynchronize());
+#undef CREATE_TRY
+    *out = s;
+    return SHARD_OK;
+}
+
+int shard_destroy(shard_t* s) {
+    if (!s) return SHARD_OK;
+    const hipError_t e = hipDeviceSynchronize();
+    free_all(s);
+    if (e != hipSuccess) return fail(SHARD_E_HIP, "hipDeviceSynchronize: %s", hipGetErrorString(e));
+    return SHARD_OK;
+}
+
+int shard_seq_alloc(shard_t* s, int32_t* seq_id) {
+    if (!s || !seq_id) return fail(SHARD_E_INVAL, "null argument");
+    for (int i = 0; i < s->kv.max_seqs; ++i)
+        if (s->seq_len[i] < 0) {
+            s->seq_len[i] = 0;
+            s->seq_pages[i] = 0;
+            *seq_id = i;
+            return SHARD_OK;
+        }
+    return fail(SHARD_E_KV_FULL, "all %d sequence slots are live", s->kv.max_seqs);
+}
+
+int shard_seq_free(shard_t* s, int32_t seq_id) {
+    if (!s) return fail(SHARD_E_INVAL, "null shard");
+    if (seq_id < 0 || seq_id >= s->kv.max_seqs || s->seq_len[seq_id] < 0)
+        return fail(SHARD_E_STATE, "seq_id %d is not live", seq_id);
+    for (int i = s->seq_pages[seq_id] - 1; i >= 0; --i)
+        s->free_pages.push_back(s->host_table[static_cast<size_t>(seq_id) * s->max_pages + i]);
+    s->seq_pages[seq_id] = 0;
+    s->seq_len[seq_id] = -1;
+    return SHARD_OK;
+}
+
+int32_t shard_seq_len(shard_t* s, int32_t seq_id) {
+    if (!s) return fail(SHARD_E_INVAL, "null shard");
+    if (seq_id < 0 || seq_id >= s->kv.max_seqs || s->seq_len[seq_id] < 0)
+        return fail(SHARD_E_STATE, "seq_id %d is not live", seq_id);
+    return s->seq_len[seq_id];
+}
+
+int shard_prefill(shard_t* s, const int32_t* seq_ids, int32_t B, int32_t T, const void* x_in, void* x_out,
+                  void* hip_stream) {
+    SeqBatch sb;
+    int rc = check_batch(s, seq_ids, B, T, false, &sb);
+    if (rc) return rc;
+    if (!x_in || !x_out) return fail(SHARD_E_INVAL, "null activation pointer");
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    grow_sequences(s, sb, T, st);
+    run_prefill(s, sb, T, static_cast<const float*>(x_in), static_cast<float*>(x_out), st);
+    for (int b = 0; b < B; ++b) s->seq_len[sb.seq[b]] += T;
+    return check_launch();
+}
+
+int shard_decode(shard_t* s, const int32_t* seq_ids, int32_t B, const void* x_in, void* x_out, void* hip_stream) {
+    SeqBatch sb;
+    int rc = check_batch(s, seq_ids, B, 1, true, &sb);
+    if (rc) return rc;
+    if (!x_in || !x_out) return fail(SHARD_E_INVAL, "null activation pointer");
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    grow_sequences(s, sb, 1, st);
+    run_decode(s, sb, static_cast<const float*>(x_in), static_cast<float*>(x_out), st);
+    for (int b = 0; b < B; ++b) s->seq_len[sb.seq[b]] += 1;
+    return check_launch();
+}
+
+int shard_timing_enable(shard_t* s, int32_t on) {
+    if (!s) return fail(SHARD_E_INVAL, "null shard");
+    Timing& t = s->timing;
+    t.on = on != 0;
+    for (int k = 0; k < SHARD_K_COUNT; ++k) {
+        t.used[k] = 0;
+        t.launches[k] = 0;
+        t.seconds[k] = 0.0;
+    }
+    return SHARD_OK;
+}
+
+int shard_timing_read(shard_t* s, int64_t launches[SHARD_K_COUNT], double seconds[SHARD_K_COUNT]) {
+    if (!s || !launches || !seconds) return fail(SHARD_E_INVAL, "null argument");
+    Timing& t = s->timing;
+    HIP_TRY(hipStreamSynchronize(t.last_stream));
+    for (int k = 0; k < SHARD_K_COUNT; ++k) {
+        for (size_t i = 0; i + 1 < t.used[k]; i += 2) {
+            float ms = 0.f;
+            HIP_TRY(hipEventElapsedTime(&ms, t.ev[k][i], t.ev[k][i + 1]));
+            t.seconds[k] += ms * 1e-3;
+            t.launches[k] += 1;
+        }
+        t.used[k] = 0;
+        launches[k] = t.launches[k];
+        seconds[k] = t.seconds[k];
+    }
+    return SHARD_OK;
+}
+
+int shard_profile(shard_t* s, int32_t B, int32_t T_prefill, int32_t n_decode, int32_t iters, shard_layer_profile* out) {
+    if (!s || !out) return fail(SHARD_E_INVAL, "null argument");
+    if (B < 1 || B > SHARD_MAX_BATCH || T_prefill < 1 || n_decode < 0 || iters < 1)
+        return fail(SHARD_E_INVAL, "bad profile shape");
+    if (static_cast<long>(B) * T_prefill > s->mmax) return fail(SHARD_E_INVAL, "B*T_prefill exceeds max_batch_tokens");
+    if (T_prefill + n_decode > s->kv.max_seq_len) return fail(SHARD_E_KV_FULL, "T_prefill + n_decode > max_seq_len");
+    int free_slots = 0;
+    for (int v : s->seq_len) free_slots += v < 0;
+    if (free_slots < B) return fail(SHARD_E_KV_FULL, "profiling needs %d free sequence slots, %d available", B, free_slots);
+
+    const int d = s->m.d_model, L = s->L;
+    const size_t n = static_cast<size_t>(B) * T_prefill * d;
+    std::vector<float> hx(n);
+    uint32_t lcg = 12345u;  // deterministic activations of unit scale
+    for (auto& v : hx) {
+        lcg = lcg * 1664525u + 1013904223u;
+        v = (static_cast<float>(lcg >> 8) / 8388608.0f - 1.0f) * 1.7320508f;
+    }
+    float *x = nullptr, *y = nullptr;
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&x), n * sizeof(float)));
+    if (hipMalloc(reinterpret_cast<void**>(&y), n * sizeof(float)) != hipSuccess) {
+        (void)hipFree(x);
+        return fail(SHARD_E_NOMEM, "profile buffers");
+    }
+    int rc = SHARD_OK;
+    std::vector<double> tp(L, 0.0), td(L, 0.0);
+    std::vector<int32_t> ids(B);
+    auto add_layer_times = [&](std::vector<double>& acc) -> bool {
+        if (hipEventSynchronize(s->layer_ev[L]) != hipSuccess) return false;
+        for (int i = 0; i < L; ++i) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, s->layer_ev[i], s->layer_ev[i + 1]) != hipSuccess) return false;
+            acc[i] += ms * 1e-3;
+        }
+        return true;
+    };
+    if (hipMemcpy(x, hx.data(), n * sizeof(float), hipMemcpyHostToDevice) != hipSuccess) rc = fail(SHARD_E_HIP, "profile upload");
+    for (int it = -1; it < iters && rc == SHARD_OK; ++it) {  // iteration -1 is an untimed warm-up
+        for (int b = 0; b < B && rc == SHARD_OK; ++b) rc = shard_seq_alloc(s, &ids[b]);
+        if (rc) break;
+        s->record_layers = true;
+        rc = shard_prefill(s, ids.data(), B, T_prefill, x, y, nullptr);
+        if (rc == SHARD_OK && it >= 0 && !add_layer_times(tp)) rc = fail(SHARD_E_HIP, "profile events");
+        for (int k = 0; k < n_decode && rc == SHARD_OK; ++k) {
+            rc = shard_decode(s, ids.data(), B, x, y, nullptr);
+            if (rc == SHARD_OK && it >= 0 && !add_layer_times(td)) rc = fail(SHARD_E_HIP, "profile events");
+        }
+        s->record_layers = false;
+        (void)hipDeviceSynchronize();
+        for (int b = 0; b < B; ++b) (void)shard_seq_free(s, ids[b]);
+    }
+    s->record_layers = false;
+    (void)hipDeviceSynchronize();
+    (void)hipFree(x);
+    (void)hipFree(y);
+    if (rc) return rc;
+    const shard_model_cfg& m = s->m;
+    const uint64_t wbytes = (static_cast<uint64_t>(s->nqkv) * d + static_cast<uint64_t>(d) * s->nq +
+                             3ull * m.ffn_dim * d) * s->es + 2ull * d * sizeof(float);
+    for (int i = 0; i < L; ++i) {
+        shard_layer_profile& p = out[i];
+        p.t_prefill_s = tp[i] / iters;
+        p.t_decode_s = n_decode ? td[i] / (static_cast<double>(iters) * n_decode) : 0.0;
+        p.t_avg_s = (p.t_prefill_s + n_decode * p.t_decode_s) / (1 + n_decode);
+        p.act_bytes_prefill = static_cast<uint64_t>(B) * T_prefill * d * sizeof(float);
+        p.act_bytes_decode = static_cast<uint64_t>(B) * d * sizeof(float);
+        p.weight_bytes = wbytes;
+        p.kv_bytes_per_token = 2ull * m.n_kv_heads * m.head_dim * s->es;
+    }
+    return SHARD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,218 @@
+"""GPU parity: libshard (HIP, through the C-ABI) against the float64 CPU oracle on the same
+seeded inputs, element by element, with max|y - y_ref| / max|y_ref| <= 1e-3 (fp32) or
+2e-2 (bf16), checked after the prefill and after every decode step."""
+import numpy as np
+import pytest
+
+from paper_2405_14371_amd import synth
+from tests import gpu_harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def chunks_for(cfg, seed, B, T, n_dec):
+    out = [np.concatenate([synth.hidden_states(cfg, seed, "prefill", 0, b, 1, T) for b in range(B)])]
+    for s in range(n_dec):
+        out.append(np.concatenate([synth.hidden_states(cfg, seed, "dec", s, b, 1, 1) for b in range(B)]))
+    return out
+
+
+def run_case(lib, cfg, n_layers, dtype, B, T, n_dec, seed=0, gains=False, page_size=16, max_seq_len=None):
+    layers = H.make_layers(cfg, seed, n_layers, dtype, gains)
+    sh = H.gpu_shard(lib, cfg, layers, dtype, max_seqs=B, max_seq_len=max_seq_len or (T + n_dec),
+                     page_size=page_size, max_batch_tokens=B * T)
+    ids = [sh.seq_alloc() for _ in range(B)]
+    chunks = chunks_for(cfg, seed, B, T, n_dec)
+    got = H.run_gpu(sh, ids, chunks)
+    want = H.run_oracle(cfg, layers, chunks)
+    H.assert_parity(got, want, H.TOL[dtype], f"{dtype} B{B} T{T}")
+    for i in ids:
+        assert sh.seq_len(i) == T + n_dec
+    sh.close()
+    return got, want
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tiny_config_prefill_32_decode_16(lib, dtype):
+    """BASELINE config 1: 2 layers, d 256, 4 heads x 64, FFN 688, batch 1, 32 + 16."""
+    run_case(lib, synth.model_cfg("tiny"), 2, dtype, B=1, T=32, n_dec=16)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ragged_sizes_random_gains_small_pages(lib, dtype):
+    """T and context lengths that are not multiples of any tile, gains != 1, 3-token pages."""
+    run_case(lib, synth.model_cfg("tiny"), 2, dtype, B=2, T=37, n_dec=5, seed=3, gains=True, page_size=3)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_grouped_query_attention(lib, dtype):
+    cfg = synth.model_cfg("tiny", n_heads=8, n_kv_heads=2, head_dim=32, ffn_dim=344)
+    run_case(lib, cfg, 2, dtype, B=3, T=45, n_dec=4, seed=5, gains=True, page_size=16)
+
+
+def test_single_token_prefill_and_page_size_one(lib):
+    run_case(lib, synth.model_cfg("tiny"), 1, "f32", B=1, T=1, n_dec=3, page_size=1)
+
+
+def test_head_dim_128_and_wide_batch_decode(lib):
+    """dh = 128 (the Llama2 head size) and a decode batch of 16 (two passes of 8 rows)."""
+    cfg = synth.model_cfg("tiny", d_model=512, n_heads=4, n_kv_heads=2, head_dim=128, ffn_dim=1024)
+    run_case(lib, cfg, 2, "f32", B=16, T=20, n_dec=3, seed=7)
+
+
+def test_long_context_spans_many_key_tiles_and_splits(lib):
+    cfg = synth.model_cfg("tiny")
+    run_case(lib, cfg, 1, "f32", B=1, T=300, n_dec=3, seed=9)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_llama2_7b_width_two_layers(lib, dtype):
+    """Full 7B layer shapes (d 4096, 32 x 128, FFN 11008): several GEMM tiles per dimension,
+    a ragged row count, and decode steps through the streaming kernels."""
+    run_case(lib, synth.model_cfg("7b"), 2, dtype, B=1, T=72, n_dec=4, seed=1)
+
+
+def test_chunked_prefill_and_ragged_decode_batch(lib):
+    """Two sequences prefilled separately to different lengths (one of them in two chunks),
+    then decoded together: positions and lengths differ inside one decode call."""
+    cfg = synth.model_cfg("tiny")
+    layers = H.make_layers(cfg, 11, 2, gains=True)
+    sh = H.gpu_shard(lib, cfg, layers, max_seqs=2, max_seq_len=64, page_size=4, max_batch_tokens=64)
+    a, b = sh.seq_alloc(), sh.seq_alloc()
+    xa = synth.hidden_states(cfg, 11, "prefill", 0, 0, 1, 33)
+    xb = synth.hidden_states(cfg, 11, "prefill", 0, 1, 1, 9)
+    ga = H.run_gpu(sh, [a], [xa[:, :20], xa[:, 20:]])
+    gb = H.run_gpu(sh, [b], [xb])
+    dec = [np.concatenate([synth.hidden_states(cfg, 11, "dec", s, m, 1, 1) for m in range(2)]) for s in range(3)]
+    torch = H.torch_mod()
+    gd = []
+    for x in dec:
+        xd = H.to_dev(x); yd = torch.empty_like(xd)
+        sh.decode([a, b], xd, yd, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        gd.append(yd.cpu().numpy())
+    o = H.orc.OracleShard(cfg, layers)
+    wa = o.forward("a", xa[0].astype(np.float64))
+    wb = o.forward("b", xb[0].astype(np.float64))
+    H.assert_parity([np.concatenate(ga, axis=1)[0]], [wa], 1e-3, "chunked prefill")
+    H.assert_parity([gb[0][0]], [wb], 1e-3, "second sequence")
+    for s, x in enumerate(dec):
+        w = np.stack([o.forward("a", x[0].astype(np.float64)), o.forward("b", x[1].astype(np.float64))])
+        H.assert_parity([gd[s]], [w], 1e-3, f"ragged decode {s}")
+    assert sh.seq_len(a) == 36 and sh.seq_len(b) == 12
+    sh.close()
+
+
+def test_shard_composition_is_exact_on_gpu(lib):
+    """Layers [0,1) then [1,2) on the handed-over activation give bit-identical results to
+    [0,2): the hand-off is fp32 and the kernels are deterministic."""
+    cfg = synth.model_cfg("tiny")
+    layers = H.make_layers(cfg, 13, 2)
+    chunks = chunks_for(cfg, 13, 1, 24, 3)
+    kv = dict(max_seqs=1, max_seq_len=32, page_size=8)
+    whole = H.gpu_shard(lib, cfg, layers, **kv)
+    first = H.gpu_shard(lib, cfg, layers[:1], layer_lo=0, **kv)
+    second = H.gpu_shard(lib, cfg, layers[1:], layer_lo=1, **kv)
+    w = H.run_gpu(whole, [whole.seq_alloc()], chunks)
+    mid = H.run_gpu(first, [first.seq_alloc()], chunks)
+    two = H.run_gpu(second, [second.seq_alloc()], mid)
+    for x, y in zip(w, two):
+        np.testing.assert_array_equal(x, y)
+    again = H.gpu_shard(lib, cfg, layers, **kv)
+    for x, y in zip(w, H.run_gpu(again, [again.seq_alloc()], chunks)):
+        np.testing.assert_array_equal(x, y)          # run-to-run determinism
+    for s in (whole, first, second, again):
+        s.close()
+
+
+def test_decode_after_prefill_matches_longer_prefill_on_gpu(lib):
+    """prefill(T) + decode(1) against prefill(T+1): two different kernel paths, same maths."""
+    cfg = synth.model_cfg("tiny")
+    layers = H.make_layers(cfg, 17, 2)
+    x = synth.hidden_states(cfg, 17, "prefill", 0, 0, 1, 41)
+    kv = dict(max_seqs=1, max_seq_len=48, page_size=16)
+    a = H.gpu_shard(lib, cfg, layers, **kv)
+    b = H.gpu_shard(lib, cfg, layers, **kv)
+    ya = H.run_gpu(a, [a.seq_alloc()], [x[:, :40], x[:, 40:]])
+    yb = H.run_gpu(b, [b.seq_alloc()], [x])
+    err = H.orc.max_rel_err(ya[1][0, 0], yb[0][0, 40])
+    assert err < 2e-5, err
+    np.testing.assert_allclose(ya[0][0], yb[0][0, :40], rtol=0, atol=1e-5 * np.abs(yb[0]).max())
+    a.close(); b.close()
+
+
+def test_output_may_alias_input_and_freed_pages_are_reused(lib):
+    cfg = synth.model_cfg("tiny")
+    layers = H.make_layers(cfg, 19, 2)
+    torch = H.torch_mod()
+    sh = H.gpu_shard(lib, cfg, layers, max_seqs=2, max_seq_len=40, page_size=4)
+    x = synth.hidden_states(cfg, 19, "prefill", 0, 0, 1, 30)
+    want = H.run_oracle(cfg, layers, [x])[0]
+    st = torch.cuda.current_stream().cuda_stream
+    for _ in range(3):                     # slot and pages are recycled each round
+        sid = sh.seq_alloc()
+        junk = sh.seq_alloc()
+        buf = H.to_dev(x)
+        sh.prefill([sid], 30, buf, buf, st)          # in place
+        torch.cuda.synchronize()
+        H.assert_parity([buf.cpu().numpy()], [want], 1e-3, "aliased")
+        sh.seq_free(junk); sh.seq_free(sid)
+    sh.close()
+
+
+def test_runtime_errors_leave_state_unchanged(lib):
+    cfg = synth.model_cfg("tiny")
+    layers = H.make_layers(cfg, 23, 1)
+    torch = H.torch_mod()
+    sh = H.gpu_shard(lib, cfg, layers, max_seqs=2, max_seq_len=16, page_size=4, max_batch_tokens=16)
+    x = H.to_dev(synth.hidden_states(cfg, 23, "prefill", 0, 0, 1, 16))
+    y = torch.empty_like(x)
+    a = sh.seq_alloc()
+
+    def expect(code, fn, *args):
+        with pytest.raises(lib.ShardError) as e:
+            fn(*args)
+        assert e.value.code == code, e.value
+
+    expect(lib.SHARD_E_STATE, sh.decode, [a], x, y)                 # decode on an empty sequence
+    expect(lib.SHARD_E_STATE, sh.prefill, [a, a], 2, x, y)          # duplicate id
+    expect(lib.SHARD_E_STATE, sh.prefill, [1], 2, x, y)             # slot 1 not live
+    expect(lib.SHARD_E_KV_FULL, sh.prefill, [a], 17, x, y)          # longer than max_seq_len...
+    expect(lib.SHARD_E_INVAL, sh.prefill, [a], 0, x, y)
+    expect(lib.SHARD_E_INVAL, sh.prefill, [a], 4, None, y)
+    assert sh.seq_len(a) == 0
+    sh.prefill([a], 12, x, y)
+    expect(lib.SHARD_E_KV_FULL, sh.prefill, [a], 5, x, y)           # 12 + 5 > 16
+    assert sh.seq_len(a) == 12
+    b = sh.seq_alloc()
+    expect(lib.SHARD_E_KV_FULL, sh.seq_alloc)
+    sh.seq_free(b)
+    expect(lib.SHARD_E_STATE, sh.seq_free, b)
+    torch.cuda.synchronize()
+    sh.close()
+
+
+def test_profile_and_kernel_timing(lib):
+    cfg = synth.model_cfg("tiny")
+    layers = H.make_layers(cfg, 29, 2)
+    sh = H.gpu_shard(lib, cfg, layers, max_seqs=1, max_seq_len=64)
+    prof = sh.profile(B=1, T_prefill=32, n_decode=4, iters=2)
+    assert len(prof) == 2
+    for p in prof:
+        assert 0 < p["t_decode_s"] < 1.0 and 0 < p["t_prefill_s"] < 1.0
+        assert p["t_avg_s"] == pytest.approx((p["t_prefill_s"] + 4 * p["t_decode_s"]) / 5)
+        assert p["act_bytes_prefill"] == 32 * 256 * 4 and p["act_bytes_decode"] == 256 * 4
+        assert p["weight_bytes"] == H.orc.params_per_layer(cfg) * 4
+        assert p["kv_bytes_per_token"] == 2 * 4 * 64 * 4
+    torch = H.torch_mod()
+    sid = sh.seq_alloc()
+    x = H.to_dev(synth.hidden_states(cfg, 29, "prefill", 0, 0, 1, 8)); y = torch.empty_like(x)
+    sh.timing_enable(True)
+    sh.prefill([sid], 8, x, y)
+    sh.decode([sid], x[:, :1].contiguous(), y[:, :1].contiguous())
+    t = sh.timing_read()
+    assert t["prefill_gemm"]["launches"] == 8 and t["prefill_attn"]["launches"] == 2
+    assert t["decode_linear"]["launches"] == 8 and t["decode_attn"]["launches"] == 2
+    assert all(v["seconds"] > 0 for k, v in t.items() if v["launches"])
+    sh.timing_enable(False)
+    sh.close()
