@@ -54,7 +54,7 @@ def algorithmic_work(cfg, wl):
     decode_bytes = L * (mat * e + gains * 4) + B * L * kv_tok * (mean_ctx + 1) + 2 * B * d * 4
     prefill_flops = 2.0 * B * T * L * mat + 2.0 * hq * dh * T * (T + 1) * L * B
     linear_bytes = {  # per launch of the streaming projection kernel, by projection
-        "qkv": (hq + 2 * hkv) * dh * d * e, "o": d * hq * dh * e, "gate_up": 2 * F * d * e, "down": d * F * e,
+        "qkv": (hq + 2 * hkv) * dh * d * e, "o": d * hq * dh * e, "gateup": 2 * F * d * e, "down": d * F * e,
     }
     gemm_flops = {k: 2.0 * B * T * v / e for k, v in linear_bytes.items()}
     return dict(decode_bytes=decode_bytes, prefill_flops=prefill_flops, linear_bytes=linear_bytes,
@@ -167,7 +167,8 @@ def main():
     one_step(False)
     kt = sh.timing_read()
     sh.timing_enable(False)
-    lin = kt["decode_linear"]
+    proj = ("qkv", "o", "gateup", "down")
+    lin = {f: sum(kt["decode_" + k][f] for k in proj) for f in ("launches", "seconds")}
     lin_bytes = sum(work["linear_bytes"].values()) * L * n_dec
     lin_gbps = lin_bytes / lin["seconds"] / 1e9
     roofline = {
@@ -177,7 +178,7 @@ def main():
         "launches": lin["launches"], "avg_launch_us": round(lin["seconds"] / max(1, lin["launches"]) * 1e6, 2),
         "algorithmic_bytes_per_launch": round(lin_bytes / max(1, lin["launches"])),
     }
-    gm = kt["prefill_gemm"]
+    gm = {f: sum(kt["prefill_" + k][f] for k in proj) for f in ("launches", "seconds")}
     gm_flops = sum(work["gemm_flops"].values()) * L
     peak_tf = MFMA_PEAK_TFLOPS[wl["dtype"]]
     roofline_prefill = {
@@ -186,7 +187,13 @@ def main():
         "frac": round(gm_flops / gm["seconds"] / 1e12 / peak_tf, 4),
         "launches": gm["launches"], "avg_launch_us": round(gm["seconds"] / max(1, gm["launches"]) * 1e6, 2),
     }
-    kernel_seconds = {k: {"launches": v["launches"], "ms": round(v["seconds"] * 1e3, 3)} for k, v in kt.items()}
+    kernel_seconds = {k: {"launches": v["launches"], "ms": round(v["seconds"] * 1e3, 3),
+                          "avg_us": round(v["seconds"] / max(1, v["launches"]) * 1e6, 2)} for k, v in kt.items()}
+    for k in proj:      # per-projection rates of the two engines
+        kernel_seconds["decode_" + k]["gbps"] = round(
+            work["linear_bytes"][k] * kt["decode_" + k]["launches"] / kt["decode_" + k]["seconds"] / 1e9, 1)
+        kernel_seconds["prefill_" + k]["tflops"] = round(
+            work["gemm_flops"][k] * kt["prefill_" + k]["launches"] / kt["prefill_" + k]["seconds"] / 1e12, 2)
     sh.close()
 
     out = {

@@ -145,17 +145,23 @@ int shard_decode(shard_t *s, const int32_t *seq_ids, int32_t B,
 int shard_profile(shard_t *s, int32_t B, int32_t T_prefill, int32_t n_decode, int32_t iters,
                   shard_layer_profile *out);
 
-/* Kernel timing for roofline reports.  While enabled, every launch of the kernel classes
- * below is bracketed by HIP events on its stream; shard_timing_read waits for the stream
- * work recorded so far, and returns launches and total seconds per class since enable.
- * Classes follow the steps of the layer; see SHARD_K_* . */
+/* Kernel timing for roofline reports.  While enabled, every kernel launch is bracketed by
+ * HIP events on its stream; shard_timing_read waits for the stream work recorded so far
+ * and returns launches and total seconds per class since enable.  The classes are the
+ * steps of the layer, separately for the autoregressive and the prefill phase. */
 enum {
-    SHARD_K_DECODE_LINEAR = 0, /* weight-streaming projections of shard_decode (QKV, O, gate/up, down) */
+    SHARD_K_DECODE_QKV = 0,     /* RMSNorm + QKV projection + RoPE + KV append */
     SHARD_K_DECODE_ATTN = 1,
-    SHARD_K_PREFILL_GEMM = 2,  /* MFMA projections of shard_prefill */
-    SHARD_K_PREFILL_ATTN = 3,
-    SHARD_K_OTHER = 4,         /* RMSNorm and bookkeeping kernels */
-    SHARD_K_COUNT = 5
+    SHARD_K_DECODE_O = 2,       /* O projection + residual */
+    SHARD_K_DECODE_GATEUP = 3,  /* RMSNorm + gate/up projection + SwiGLU */
+    SHARD_K_DECODE_DOWN = 4,    /* down projection + residual */
+    SHARD_K_PREFILL_NORM = 5,   /* both RMSNorms */
+    SHARD_K_PREFILL_QKV = 6,    /* QKV GEMM + RoPE + KV append */
+    SHARD_K_PREFILL_ATTN = 7,
+    SHARD_K_PREFILL_O = 8,
+    SHARD_K_PREFILL_GATEUP = 9,
+    SHARD_K_PREFILL_DOWN = 10,
+    SHARD_K_COUNT = 11
 };
 int shard_timing_enable(shard_t *s, int32_t on);
 int shard_timing_read(shard_t *s, int64_t launches[SHARD_K_COUNT], double seconds[SHARD_K_COUNT]);

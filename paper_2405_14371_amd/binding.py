@@ -14,8 +14,9 @@ LIB_PATH = os.path.join(_HERE, "libshard.so")
 SHARD_OK, SHARD_E_INVAL, SHARD_E_NOMEM, SHARD_E_KV_FULL, SHARD_E_STATE, SHARD_E_HIP = 0, -1, -2, -3, -4, -5
 SHARD_F32, SHARD_BF16 = 0, 1
 SHARD_MAX_BATCH = 64
-K_DECODE_LINEAR, K_DECODE_ATTN, K_PREFILL_GEMM, K_PREFILL_ATTN, K_OTHER, K_COUNT = 0, 1, 2, 3, 4, 5
-KERNEL_CLASSES = ("decode_linear", "decode_attn", "prefill_gemm", "prefill_attn", "other")
+KERNEL_CLASSES = ("decode_qkv", "decode_attn", "decode_o", "decode_gateup", "decode_down", "prefill_norm",
+                  "prefill_qkv", "prefill_attn", "prefill_o", "prefill_gateup", "prefill_down")
+K_COUNT = len(KERNEL_CLASSES)
 
 EXPORTS = (
     "shard_create", "shard_destroy", "shard_seq_alloc", "shard_seq_free", "shard_seq_len",
@@ -63,6 +64,9 @@ def load():
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2405_14371_amd.build` "
                            "(or __graft_entry__.build()) first; there is no CPU fallback")
+    # PyTorch ships its own HIP runtime under the same soname as the system one; it must
+    # be the first (and only) copy in the process, or torch finds no device afterwards.
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, i32 = C.c_void_p, C.c_int32
     lib.shard_create.argtypes = [C.POINTER(vp), C.POINTER(ModelCfg), C.POINTER(KvCfg), i32, i32,

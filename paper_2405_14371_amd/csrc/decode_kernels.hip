@@ -195,13 +195,16 @@ void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t
 // ---------------------------------------------------------------------------------------
 // Attention of one new token per sequence over its cached keys/values.
 // Grid (nsplit, nb*hq).  A workgroup takes one slice of the context of one (sequence,
-// query head); TPT = DH/VEC adjacent lanes share a token (one 16-byte load each), so a
-// workgroup handles 256/TPT tokens per trip.  Each lane group keeps its own running
-// (max, sum, weighted V) - softmax statistics are merged with lane shuffles inside the
-// group, through LDS across groups, and across context slices by the workgroup that
-// finishes last (fixed slice order, so the result does not depend on which one that is).
+// query head); TPT = DH/VEC adjacent lanes share a token (one 16-byte load each), and each
+// lane group keeps TU tokens in flight, so a workgroup covers TU*256/TPT tokens per trip.
+// Each lane group keeps its own running (max, sum, weighted V) - softmax statistics are
+// merged with lane shuffles inside the group, through LDS across groups, and across
+// context slices by the workgroup that finishes last (fixed slice order, so the result
+// does not depend on which one that is).
 // ---------------------------------------------------------------------------------------
-template <typename KT, int DH>
+constexpr int ATTN_MAX_SPLIT = 32;
+
+template <typename KT, int DH, int TU>
 __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttn a, SeqBatch sb) {
     constexpr int VEC = Elem<KT>::VEC;
     constexpr int TPT = DH / VEC;
@@ -230,27 +233,48 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttn a, SeqBatch
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
 
-    for (int u = u_begin + g; u < u_end; u += GROUPS) {
-        const int page = bt[u / a.kv.page];
-        const size_t at = ((static_cast<size_t>(page) * a.kv.hkv + hk) * a.kv.page + u % a.kv.page) * DH + e0;
-        Vec16<KT> kv, vv;
-        kv.load(kp + at);
-        vv.load(vp + at);
-        float s = 0.f;
+    for (int u0 = u_begin + g; u0 < u_end; u0 += GROUPS * TU) {
+        Vec16<KT> kv[TU], vv[TU];
+        bool ok[TU];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) s = fmaf(qv[e], kv.v[e], s);
+        for (int i = 0; i < TU; ++i) {
+            const int u = u0 + i * GROUPS;
+            ok[i] = u < u_end;
+            const int uc = ok[i] ? u : u0;
+            const int page = bt[uc / a.kv.page];
+            const size_t at = ((static_cast<size_t>(page) * a.kv.hkv + hk) * a.kv.page + uc % a.kv.page) * DH + e0;
+            kv[i].load(kp + at);
+            vv[i].load(vp + at);
+        }
+        float s[TU], mn = m;
 #pragma unroll
-        for (int o = TPT / 2; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
-        const float mn = fmaxf(m, s);
-        const float corr = __expf(m - mn), p = __expf(s - mn);
-        l = l * corr + p;
+        for (int i = 0; i < TU; ++i) {
+            float d = 0.f;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] = fmaf(p, vv.v[e], acc[e] * corr);
+            for (int e = 0; e < VEC; ++e) d = fmaf(qv[e], kv[i].v[e], d);
+#pragma unroll
+            for (int o = TPT / 2; o >= 1; o >>= 1) d += __shfl_xor(d, o, 64);
+            s[i] = ok[i] ? d : -INFINITY;
+            mn = fmaxf(mn, s[i]);
+        }
+        const float corr = __expf(m - mn);  // first trip: exp(-inf) = 0
+        l *= corr;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] *= corr;
+#pragma unroll
+        for (int i = 0; i < TU; ++i) {
+            const float p = __expf(s[i] - mn);
+            l += p;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] = fmaf(p, vv[i].v[e], acc[e]);
+        }
         m = mn;
     }
 
     __shared__ float s_m[GROUPS], s_l[GROUPS];
     __shared__ float s_acc[GROUPS][DH];
+    __shared__ float s_w[ATTN_MAX_SPLIT];
+    __shared__ float s_L;
     __shared__ int s_ticket;
     if (tid % TPT == 0) { s_m[g] = m; s_l[g] = l; }
 #pragma unroll
@@ -259,8 +283,10 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttn a, SeqBatch
 
     float M = -INFINITY, L = 0.f, O = 0.f;
     if (tid < DH) {
+#pragma unroll
         for (int i = 0; i < GROUPS; ++i) M = fmaxf(M, s_m[i]);
         if (M > -INFINITY) {
+#pragma unroll
             for (int i = 0; i < GROUPS; ++i) {
                 const float w = __expf(s_m[i] - M);  // empty groups: exp(-inf) = 0
                 L = fmaf(s_l[i], w, L);
@@ -285,18 +311,32 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttn a, SeqBatch
     __syncthreads();
     if (s_ticket != a.nsplit - 1) return;
     __threadfence();
+    // Last workgroup of this (sequence, head): merge the slices.  Lanes 0..31 fetch the
+    // slice statistics in parallel; the weighted sum over slices runs in slice order.
+    if (tid < ATTN_MAX_SPLIT) {
+        const bool have = tid < a.nsplit;
+        const float ms = have ? a.part_ml[(pbase + tid) * 2] : -INFINITY;
+        const float ls = have ? a.part_ml[(pbase + tid) * 2 + 1] : 0.f;
+        float mx = ms;
+#pragma unroll
+        for (int o = 16; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+        const float w = ms == -INFINITY ? 0.f : __expf(ms - mx);  // slices without tokens weigh 0
+        float lw = ls * w;
+#pragma unroll
+        for (int o = 16; o >= 1; o >>= 1) lw += __shfl_xor(lw, o, 64);
+        s_w[tid] = w;
+        if (tid == 0) s_L = lw;
+    }
+    __syncthreads();
     if (tid < DH) {
-        float Mx = -INFINITY;
-        for (int s = 0; s < a.nsplit; ++s) Mx = fmaxf(Mx, a.part_ml[(pbase + s) * 2]);
-        float Lx = 0.f, Ox = 0.f;
-        for (int s = 0; s < a.nsplit; ++s) {
-            const float ms = a.part_ml[(pbase + s) * 2];
-            if (ms == -INFINITY) continue;  // slice held no tokens
-            const float w = __expf(ms - Mx);
-            Lx = fmaf(a.part_ml[(pbase + s) * 2 + 1], w, Lx);
-            Ox = fmaf(a.part_o[(pbase + s) * DH + tid], w, Ox);
-        }
-        op[tid] = Ox / Lx;
+        float po[ATTN_MAX_SPLIT];
+#pragma unroll
+        for (int s = 0; s < ATTN_MAX_SPLIT; ++s)
+            po[s] = s < a.nsplit ? a.part_o[(pbase + s) * DH + tid] : 0.f;
+        float ox = 0.f;
+#pragma unroll
+        for (int s = 0; s < ATTN_MAX_SPLIT; ++s) ox = fmaf(po[s], s_w[s], ox);
+        op[tid] = ox / s_L;
     }
     if (tid == 0) a.counters[bh] = 0;
 }
@@ -306,16 +346,16 @@ void launch_decode_attn(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st)
     const bool f32 = a.kv_dtype == DT_F32;
     switch (a.kv.dh) {
         case 32:
-            if (f32) hipLaunchKernelGGL((decode_attn_kernel<float, 32>), grid, block, 0, st, a, sb);
-            else hipLaunchKernelGGL((decode_attn_kernel<bf16_t, 32>), grid, block, 0, st, a, sb);
+            if (f32) hipLaunchKernelGGL((decode_attn_kernel<float, 32, 4>), grid, block, 0, st, a, sb);
+            else hipLaunchKernelGGL((decode_attn_kernel<bf16_t, 32, 4>), grid, block, 0, st, a, sb);
             break;
         case 64:
-            if (f32) hipLaunchKernelGGL((decode_attn_kernel<float, 64>), grid, block, 0, st, a, sb);
-            else hipLaunchKernelGGL((decode_attn_kernel<bf16_t, 64>), grid, block, 0, st, a, sb);
+            if (f32) hipLaunchKernelGGL((decode_attn_kernel<float, 64, 4>), grid, block, 0, st, a, sb);
+            else hipLaunchKernelGGL((decode_attn_kernel<bf16_t, 64, 4>), grid, block, 0, st, a, sb);
             break;
         default:
-            if (f32) hipLaunchKernelGGL((decode_attn_kernel<float, 128>), grid, block, 0, st, a, sb);
-            else hipLaunchKernelGGL((decode_attn_kernel<bf16_t, 128>), grid, block, 0, st, a, sb);
+            if (f32) hipLaunchKernelGGL((decode_attn_kernel<float, 128, 4>), grid, block, 0, st, a, sb);
+            else hipLaunchKernelGGL((decode_attn_kernel<bf16_t, 128, 4>), grid, block, 0, st, a, sb);
             break;
     }
 }

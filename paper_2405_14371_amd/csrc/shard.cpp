@@ -227,14 +227,14 @@ void run_prefill(shard* s, const SeqBatch& sb, int T, const float* x_in, float* 
         const LayerDev& l = s->layers[li];
         const float* x = li == 0 ? x_in : x_out;
         {
-            Bracket t(s, SHARD_K_OTHER, st);
+            Bracket t(s, SHARD_K_PREFILL_NORM, st);
             launch_rmsnorm(x, l.g_attn, m.rms_eps, s->h, dt, M, m.d_model, st);
         }
         PrefillGemm g{};
         g.M = M; g.dt = dt; g.T = T; g.hq = m.n_heads; g.kv = kv_view(s, li); g.rope = s->rope;
         g.A = s->h; g.W = l.wqkv; g.N = s->nqkv; g.K = m.d_model; g.epi = EPI_QKV; g.q = s->q;
         {
-            Bracket t(s, SHARD_K_PREFILL_GEMM, st);
+            Bracket t(s, SHARD_K_PREFILL_QKV, st);
             launch_prefill_gemm(g, sb, st);
         }
         PrefillAttn at{};
@@ -246,21 +246,21 @@ void run_prefill(shard* s, const SeqBatch& sb, int T, const float* x_in, float* 
         }
         g.A = s->o; g.W = l.wo; g.N = m.d_model; g.K = s->nq; g.epi = EPI_RESID; g.resid = x; g.out = x_out;
         {
-            Bracket t(s, SHARD_K_PREFILL_GEMM, st);
+            Bracket t(s, SHARD_K_PREFILL_O, st);
             launch_prefill_gemm(g, sb, st);
         }
         {
-            Bracket t(s, SHARD_K_OTHER, st);
+            Bracket t(s, SHARD_K_PREFILL_NORM, st);
             launch_rmsnorm(x_out, l.g_ffn, m.rms_eps, s->h, dt, M, m.d_model, st);
         }
         g.A = s->h; g.W = l.wgu; g.N = 2 * m.ffn_dim; g.K = m.d_model; g.epi = EPI_SWIGLU; g.out_act = s->f;
         {
-            Bracket t(s, SHARD_K_PREFILL_GEMM, st);
+            Bracket t(s, SHARD_K_PREFILL_GATEUP, st);
             launch_prefill_gemm(g, sb, st);
         }
         g.A = s->f; g.W = l.wd; g.N = m.d_model; g.K = m.ffn_dim; g.epi = EPI_RESID; g.resid = x_out; g.out = x_out;
         {
-            Bracket t(s, SHARD_K_PREFILL_GEMM, st);
+            Bracket t(s, SHARD_K_PREFILL_DOWN, st);
             launch_prefill_gemm(g, sb, st);
         }
         mark_layer(s, li + 1, st);
@@ -271,7 +271,7 @@ int pick_nsplit(const shard* s, const SeqBatch& sb) {
     int ctx = 1;
     for (int b = 0; b < sb.n; ++b) ctx = ctx > sb.pos[b] + 1 ? ctx : sb.pos[b] + 1;
     const int units = sb.n * s->m.n_heads;
-    int n = (1024 + units - 1) / units;            // aim at ~4 workgroups per compute unit
+    int n = (512 + units - 1) / units;             // aim at ~2 workgroups per compute unit
     const int by_len = (ctx + 31) / 32;             // at least 32 tokens per slice
     if (n > by_len) n = by_len;
     if (n > s->nsplit_max) n = s->nsplit_max;
@@ -299,7 +299,7 @@ void run_decode(shard* s, const SeqBatch& sb, const float* x_in, float* x_out, h
             d.W = l.wqkv; d.N = s->nqkv; d.K = m.d_model; d.wt = dt; d.nb = nb;
             d.x = x + static_cast<size_t>(b0) * m.d_model; d.gain = l.g_attn; d.eps = m.rms_eps;
             d.epi = EPI_QKV; d.q = s->q + static_cast<size_t>(b0) * s->nq; d.hq = m.n_heads; d.kv = kvv; d.rope = s->rope;
-            Bracket t(s, SHARD_K_DECODE_LINEAR, st);
+            Bracket t(s, SHARD_K_DECODE_QKV, st);
             launch_decode_linear(d, sub, st);
         }
         {
@@ -315,7 +315,7 @@ void run_decode(shard* s, const SeqBatch& sb, const float* x_in, float* x_out, h
             d.W = l.wo; d.N = m.d_model; d.K = s->nq; d.wt = dt; d.nb = nb;
             d.x = o + static_cast<size_t>(b0) * s->nq; d.epi = EPI_RESID;
             d.resid = x + static_cast<size_t>(b0) * m.d_model; d.out = x_out + static_cast<size_t>(b0) * m.d_model;
-            Bracket t(s, SHARD_K_DECODE_LINEAR, st);
+            Bracket t(s, SHARD_K_DECODE_O, st);
             launch_decode_linear(d, sb, st);
         }
         for (int b0 = 0; b0 < B; b0 += 8) {
@@ -324,7 +324,7 @@ void run_decode(shard* s, const SeqBatch& sb, const float* x_in, float* x_out, h
             d.W = l.wgu; d.N = 2 * m.ffn_dim; d.K = m.d_model; d.wt = dt; d.nb = nb;
             d.x = x_out + static_cast<size_t>(b0) * m.d_model; d.gain = l.g_ffn; d.eps = m.rms_eps;
             d.epi = EPI_SWIGLU; d.out = f + static_cast<size_t>(b0) * m.ffn_dim;
-            Bracket t(s, SHARD_K_DECODE_LINEAR, st);
+            Bracket t(s, SHARD_K_DECODE_GATEUP, st);
             launch_decode_linear(d, sb, st);
         }
         for (int b0 = 0; b0 < B; b0 += 8) {
@@ -333,7 +333,7 @@ void run_decode(shard* s, const SeqBatch& sb, const float* x_in, float* x_out, h
             d.W = l.wd; d.N = m.d_model; d.K = m.ffn_dim; d.wt = dt; d.nb = nb;
             d.x = f + static_cast<size_t>(b0) * m.ffn_dim; d.epi = EPI_RESID;
             d.resid = x_out + static_cast<size_t>(b0) * m.d_model; d.out = x_out + static_cast<size_t>(b0) * m.d_model;
-            Bracket t(s, SHARD_K_DECODE_LINEAR, st);
+            Bracket t(s, SHARD_K_DECODE_DOWN, st);
             launch_decode_linear(d, sb, st);
         }
         mark_layer(s, li + 1, st);
