@@ -179,9 +179,17 @@ static void launch_dl(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st)
     hipLaunchKernelGGL((decode_linear_kernel<WT, NB, R, U>), dim3(grid), dim3(256), 0, st, a, sb);
 }
 
+// (rows per workgroup, chunks in flight) from a sweep on MI355X over the Llama2 shapes:
+// many small workgroups win; wide matrices like more rows per workgroup, bf16 rows
+// (half the bytes) like more rows still.
 template <typename WT>
 static void launch_dl_t(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
-    if (a.nb == 1) launch_dl<WT, 1, 4, 4>(a, sb, st);
+    constexpr bool f32 = sizeof(WT) == 4;
+    if (a.nb == 1) {
+        if (a.N >= 8192) { if (f32) launch_dl<WT, 1, 4, 1>(a, sb, st); else launch_dl<WT, 1, 8, 1>(a, sb, st); }
+        else if (a.K > 8192) { if (f32) launch_dl<WT, 1, 2, 2>(a, sb, st); else launch_dl<WT, 1, 4, 2>(a, sb, st); }
+        else { if (f32) launch_dl<WT, 1, 2, 4>(a, sb, st); else launch_dl<WT, 1, 4, 1>(a, sb, st); }
+    }
     else if (a.nb == 2) launch_dl<WT, 2, 4, 2>(a, sb, st);
     else if (a.nb <= 4) launch_dl<WT, 4, 4, 2>(a, sb, st);
     else launch_dl<WT, 8, 4, 1>(a, sb, st);
@@ -198,9 +206,9 @@ void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t
 // query head); TPT = DH/VEC adjacent lanes share a token (one 16-byte load each), and each
 // lane group keeps TU tokens in flight, so a workgroup covers TU*256/TPT tokens per trip.
 // Each lane group keeps its own running (max, sum, weighted V) - softmax statistics are
-// merged with lane shuffles inside the group, through LDS across groups, and across
-// context slices by the workgroup that finishes last (fixed slice order, so the result
-// does not depend on which one that is).
+// merged with lane shuffles inside the group and through LDS across groups; the slices
+// of one (sequence, head) are merged by decode_attn_merge_kernel in slice order (a second
+// launch: a device-wide fence per workgroup costs far more than a kernel boundary).
 // ---------------------------------------------------------------------------------------
 constexpr int ATTN_MAX_SPLIT = 32;
 
@@ -273,9 +281,6 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttn a, SeqBatch
 
     __shared__ float s_m[GROUPS], s_l[GROUPS];
     __shared__ float s_acc[GROUPS][DH];
-    __shared__ float s_w[ATTN_MAX_SPLIT];
-    __shared__ float s_L;
-    __shared__ int s_ticket;
     if (tid % TPT == 0) { s_m[g] = m; s_l[g] = l; }
 #pragma unroll
     for (int e = 0; e < VEC; ++e) s_acc[g][e0 + e] = acc[e];
@@ -305,14 +310,16 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttn a, SeqBatch
         a.part_ml[(pbase + split) * 2] = M;
         a.part_ml[(pbase + split) * 2 + 1] = L;
     }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) s_ticket = atomicAdd(&a.counters[bh], 1);
-    __syncthreads();
-    if (s_ticket != a.nsplit - 1) return;
-    __threadfence();
-    // Last workgroup of this (sequence, head): merge the slices.  Lanes 0..31 fetch the
-    // slice statistics in parallel; the weighted sum over slices runs in slice order.
+}
+
+// Merge of the context slices of one (sequence, head): grid nb*hq, DH threads.  Lanes
+// 0..31 fetch the slice statistics in parallel; the weighted sum runs in slice order.
+template <int DH>
+__global__ __launch_bounds__(DH) void decode_attn_merge_kernel(DecodeAttn a) {
+    const int tid = threadIdx.x, bh = blockIdx.x;
+    const size_t pbase = static_cast<size_t>(bh) * a.nsplit;
+    __shared__ float s_w[ATTN_MAX_SPLIT];
+    __shared__ float s_L;
     if (tid < ATTN_MAX_SPLIT) {
         const bool have = tid < a.nsplit;
         const float ms = have ? a.part_ml[(pbase + tid) * 2] : -INFINITY;
@@ -328,36 +335,41 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttn a, SeqBatch
         if (tid == 0) s_L = lw;
     }
     __syncthreads();
-    if (tid < DH) {
-        float po[ATTN_MAX_SPLIT];
+    float po[ATTN_MAX_SPLIT];
 #pragma unroll
-        for (int s = 0; s < ATTN_MAX_SPLIT; ++s)
-            po[s] = s < a.nsplit ? a.part_o[(pbase + s) * DH + tid] : 0.f;
-        float ox = 0.f;
+    for (int s = 0; s < ATTN_MAX_SPLIT; ++s) po[s] = s < a.nsplit ? a.part_o[(pbase + s) * DH + tid] : 0.f;
+    float ox = 0.f;
 #pragma unroll
-        for (int s = 0; s < ATTN_MAX_SPLIT; ++s) ox = fmaf(po[s], s_w[s], ox);
-        op[tid] = ox / s_L;
-    }
-    if (tid == 0) a.counters[bh] = 0;
+    for (int s = 0; s < ATTN_MAX_SPLIT; ++s) ox = fmaf(po[s], s_w[s], ox);
+    a.o[static_cast<size_t>(bh) * DH + tid] = ox / s_L;
 }
 
 void launch_decode_attn(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st) {
     const dim3 grid(a.nsplit, a.nb * a.hq), block(256);
     const bool f32 = a.kv_dtype == DT_F32;
+    const int units = a.nb * a.hq;
     switch (a.kv.dh) {
         case 32:
             if (f32) hipLaunchKernelGGL((decode_attn_kernel<float, 32, 4>), grid, block, 0, st, a, sb);
             else hipLaunchKernelGGL((decode_attn_kernel<bf16_t, 32, 4>), grid, block, 0, st, a, sb);
+            if (a.nsplit > 1) hipLaunchKernelGGL(decode_attn_merge_kernel<32>, dim3(units), dim3(32), 0, st, a);
             break;
         case 64:
             if (f32) hipLaunchKernelGGL((decode_attn_kernel<float, 64, 4>), grid, block, 0, st, a, sb);
             else hipLaunchKernelGGL((decode_attn_kernel<bf16_t, 64, 4>), grid, block, 0, st, a, sb);
+            if (a.nsplit > 1) hipLaunchKernelGGL(decode_attn_merge_kernel<64>, dim3(units), dim3(64), 0, st, a);
             break;
         default:
             if (f32) hipLaunchKernelGGL((decode_attn_kernel<float, 128, 4>), grid, block, 0, st, a, sb);
             else hipLaunchKernelGGL((decode_attn_kernel<bf16_t, 128, 4>), grid, block, 0, st, a, sb);
+            if (a.nsplit > 1) hipLaunchKernelGGL(decode_attn_merge_kernel<128>, dim3(units), dim3(128), 0, st, a);
             break;
     }
+}
+
+int decode_attn_tokens_per_trip(int kv_dtype, int dh) {
+    const int vec = kv_dtype == DT_F32 ? 4 : 8;
+    return 4 * 256 / (dh / vec);
 }
 
 __global__ void table_update_kernel(int32_t* table, TableUpdate u) {

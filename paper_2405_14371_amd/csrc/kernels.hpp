@@ -56,9 +56,10 @@ struct DecodeAttn {
     int32_t nsplit;        // context splits per (sequence, head)
     float* part_o;         // [nb*hq, nsplit, dh]
     float* part_ml;        // [nb*hq, nsplit, 2]
-    int32_t* counters;     // [nb*hq], zero between launches
 };
 void launch_decode_attn(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st);
+// context tokens one workgroup of the decode attention kernel covers per trip
+int decode_attn_tokens_per_trip(int kv_dtype, int dh);
 
 // rows of x [M, d] fp32 -> RMSNorm -> out [M, d] in out_dtype
 void launch_rmsnorm(const float* x, const float* gain, float eps, void* out, int32_t out_dtype,

@@ -83,7 +83,6 @@ struct shard {
     void* f = nullptr;     // [mmax, F]      SwiGLU output   (same)
     float* part_o = nullptr;
     float* part_ml = nullptr;
-    int32_t* counters = nullptr;
     int nsplit_max = 32;
     Timing timing;
     std::vector<hipEvent_t> layer_ev;  // L+1 events, used by shard_profile
@@ -98,7 +97,7 @@ void free_all(shard* s) {
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
     }
-    void* ptrs[] = {s->rope, s->block_table, s->h, s->q, s->o, s->f, s->part_o, s->part_ml, s->counters};
+    void* ptrs[] = {s->rope, s->block_table, s->h, s->q, s->o, s->f, s->part_o, s->part_ml};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     for (auto& v : s->timing.ev)
@@ -267,13 +266,16 @@ void run_prefill(shard* s, const SeqBatch& sb, int T, const float* x_in, float* 
     }
 }
 
+// Context slices per (sequence, head): one trip of the kernel's token loop per slice,
+// unless that would put more than ~2048 workgroups on the device.
 int pick_nsplit(const shard* s, const SeqBatch& sb) {
     int ctx = 1;
     for (int b = 0; b < sb.n; ++b) ctx = ctx > sb.pos[b] + 1 ? ctx : sb.pos[b] + 1;
     const int units = sb.n * s->m.n_heads;
-    int n = (512 + units - 1) / units;             // aim at ~2 workgroups per compute unit
-    const int by_len = (ctx + 31) / 32;             // at least 32 tokens per slice
-    if (n > by_len) n = by_len;
+    const int trip = decode_attn_tokens_per_trip(s->m.weight_dtype == SHARD_F32 ? DT_F32 : DT_BF16, s->m.head_dim);
+    int n = (ctx + trip - 1) / trip;
+    const int cap = (2048 + units - 1) / units;
+    if (n > cap) n = cap;
     if (n > s->nsplit_max) n = s->nsplit_max;
     return n < 1 ? 1 : n;
 }
@@ -305,7 +307,7 @@ void run_decode(shard* s, const SeqBatch& sb, const float* x_in, float* x_out, h
         {
             DecodeAttn a{};
             a.q = s->q; a.o = o; a.nb = B; a.hq = m.n_heads; a.kv_dtype = dt; a.kv = kvv;
-            a.nsplit = pick_nsplit(s, sb); a.part_o = s->part_o; a.part_ml = s->part_ml; a.counters = s->counters;
+            a.nsplit = pick_nsplit(s, sb); a.part_o = s->part_o; a.part_ml = s->part_ml;
             Bracket t(s, SHARD_K_DECODE_ATTN, st);
             launch_decode_attn(a, sb, st);
         }
@@ -451,8 +453,6 @@ int shard_create(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg
     const size_t units = static_cast<size_t>(SHARD_MAX_BATCH) * model->n_heads;
     CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&s->part_o), units * s->nsplit_max * dh * sizeof(float)));
     CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&s->part_ml), units * s->nsplit_max * 2 * sizeof(float)));
-    CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&s->counters), units * sizeof(int32_t)));
-    CREATE_TRY(hipMemset(s->counters, 0, units * sizeof(int32_t)));
     s->layer_ev.resize(L + 1);
     for (auto& e : s->layer_ev) e = nullptr;
     for (auto& e : s->layer_ev) CREATE_TRY(hipEventCreate(&e));
