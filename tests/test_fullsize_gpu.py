@@ -1,0 +1,87 @@
+"""Full-size parity: the workloads of the benchmark spec at their real sizes, in the launch
+configuration bench.py times, against stored oracle outputs.
+
+The expected values in tests/golden/<name>.npz were written by tests/golden/make_golden.py,
+which calls only the CPU oracle; they hold a sample of output rows (first, second, middle
+and last tokens of the prefill; first, second, middle and last decode steps) in float64,
+plus checksums of the inputs so that a change of the input generator cannot go unnoticed.
+Every sampled row depends on every layer, on the whole KV cache below it and - for the
+decode rows - on the paged cache written by prefill and by all earlier decode steps."""
+import os
+
+import numpy as np
+import pytest
+
+from paper_2405_14371_amd import synth
+from tests import gpu_harness as H
+from tests.golden import make_golden as G
+
+pytestmark = pytest.mark.gpu
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def run_fullsize(lib, name, seqs_on_gpu, page_size=16):
+    path = os.path.join(GOLDEN, f"{name}.npz")
+    if not os.path.exists(path):
+        pytest.skip(f"{path} not generated")
+    gold = np.load(path)
+    wl = G.WORKLOADS[name]
+    cfg = synth.model_cfg(wl["model"])
+    torch = H.torch_mod()
+    tol = H.TOL[wl["dtype"]]
+    T, n_dec = wl["T"], wl["n_dec"]
+    pre_rows, dec_rows = gold["pre_rows"], gold["dec_rows"]
+    gold_seqs = [int(s) for s in gold["seqs"]]
+
+    # inputs of every sequence the GPU runs; checksums only exist for the oracle's sequences
+    xs = {s: G.inputs(cfg, wl, s) for s in seqs_on_gpu}
+    for i, s in enumerate(gold_seqs):
+        got = G.checksum(xs[s][0]) + G.checksum(xs[s][1])
+        assert got == pytest.approx(float(gold["input_checksum"][i]), rel=1e-12), "input generator drifted"
+
+    wd = lib.SHARD_F32 if wl["dtype"] == "f32" else lib.SHARD_BF16
+    layers, wsum = [], 0.0
+    for layer in range(wl["layers"]):
+        lw = synth.layer_weights(cfg, wl["seed"], layer, wl["dtype"])
+        wsum += G.checksum(lw["wq"][:8]) + G.checksum(lw["w_down"][-8:])
+        layers.append(lib.pack_layers([lw], wd)[0])
+    assert wsum == pytest.approx(float(gold["weight_checksum"]), rel=1e-12), "weight generator drifted"
+    B = len(seqs_on_gpu)
+    sh = lib.Shard(cfg, layers, 0, weight_dtype=wd, max_seqs=B, max_seq_len=T + n_dec, page_size=page_size,
+                   max_batch_tokens=B * T)
+    del layers
+    ids = [sh.seq_alloc() for _ in range(B)]
+    st = torch.cuda.current_stream().cuda_stream
+    xp = torch.from_numpy(np.stack([xs[s][0] for s in seqs_on_gpu])).cuda()           # [B, T, d]
+    xd = torch.from_numpy(np.stack([xs[s][1] for s in seqs_on_gpu], axis=1)).cuda()   # [n_dec, B, d]
+    yp, yd = torch.empty_like(xp), torch.empty_like(xd)
+    sh.prefill(ids, T, xp, yp, st)
+    for s in range(n_dec):
+        sh.decode(ids, xd[s], yd[s], st)
+    torch.cuda.synchronize()
+    yp, yd = yp.cpu().numpy().astype(np.float64), yd.cpu().numpy().astype(np.float64)
+    sh.close()
+    assert np.all(np.isfinite(yp)) and np.all(np.isfinite(yd))
+
+    worst = 0.0
+    for s in gold_seqs:
+        b = seqs_on_gpu.index(s)
+        # the metric's denominator is the largest magnitude of the call's output tensor
+        err_p = np.max(np.abs(yp[b][pre_rows] - gold[f"prefill_{s}"])) / float(gold[f"prefill_absmax_{s}"])
+        assert err_p <= tol, f"{name} seq {s}: prefill max rel err {err_p:.3e} > {tol}"
+        for i, step in enumerate(dec_rows):
+            err_d = np.max(np.abs(yd[step, b] - gold[f"decode_{s}"][i])) / float(gold[f"decode_absmax_{s}"][i])
+            assert err_d <= tol, f"{name} seq {s}: decode step {step} max rel err {err_d:.3e} > {tol}"
+            worst = max(worst, err_d)
+        worst = max(worst, err_p)
+    print(f"{name}: worst max-rel-err {worst:.3e} (tolerance {tol})")
+
+
+def test_config2_llama2_7b_layers_0_7_fp32_512_plus_128(lib):
+    """The workload bench.py times: 8 layers of the 7B shape, fp32, batch 1, 512 + 128."""
+    run_fullsize(lib, "c2", [0])
+
+
+def test_config3_llama2_7b_32_layers_bf16_1024_plus_256(lib):
+    """The whole 7B stack as one shard, bf16 weights and cache, batch 1, 1024 + 256."""
+    run_fullsize(lib, "c3", [0])
