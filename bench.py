@@ -171,10 +171,18 @@ def main():
     lin = {f: sum(kt["decode_" + k][f] for k in proj) for f in ("launches", "seconds")}
     lin_bytes = sum(work["linear_bytes"].values()) * L * n_dec
     lin_gbps = lin_bytes / lin["seconds"] / 1e9
+    # HBM bytes per launch from rocprofv3 PMC runs of this same command (FETCH_SIZE and
+    # WRITE_SIZE, scaled by what they read for a copy of known size); see profiles/
+    traffic = None
+    try:
+        with open(os.path.join(ROOT, "profiles", "pmc_traffic.json")) as fh:
+            traffic = json.load(fh)[args.workload]["decode_linear_kernel"]["traffic_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        pass
     roofline = {
         "kernel": "decode_linear_kernel (weight-streaming projections of shard_decode)",
         "bound": "hbm", "achieved": round(lin_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-        "frac": round(lin_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+        "frac": round(lin_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
         "launches": lin["launches"], "avg_launch_us": round(lin["seconds"] / max(1, lin["launches"]) * 1e6, 2),
         "algorithmic_bytes_per_launch": round(lin_bytes / max(1, lin["launches"])),
     }
