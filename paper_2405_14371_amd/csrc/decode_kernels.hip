@@ -201,6 +201,132 @@ void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t
 }
 
 // ---------------------------------------------------------------------------------------
+// Linear layer for 9..16 activation rows with bf16 weights: at 16 FMAs per weight element
+// the vector ALUs could no longer keep up with the HBM stream, so the products run on the
+// matrix cores: D[n][b] = sum_k W[n][k] x[b][k] with v_mfma_f32_16x16x32_bf16, the 16
+// activation rows filling the MFMA's second dimension exactly.
+// A workgroup owns 32 consecutive rows of W (two MFMA row tiles); its four waves split K
+// in interleaved 64-element blocks and meet in LDS (fixed order).  Lane (row = lane%16,
+// g = lane/16) supplies elements 32*j + 8*g + (0..7) of a block to MFMA j on both operands,
+// so every load instruction reads 64 contiguous bytes per row.  Activations arrive already
+// rounded to bf16 (and normalised where the step needs it).
+// ---------------------------------------------------------------------------------------
+typedef __bf16 bf16x8_d __attribute__((ext_vector_type(8)));
+typedef float f32x4_d __attribute__((ext_vector_type(4)));
+
+template <int U>
+__global__ __launch_bounds__(256) void decode_linear_mfma_kernel(DecodeLinear a, SeqBatch sb) {
+    constexpr int ROWS = 32;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, g = lane >> 4;
+    const int row0 = blockIdx.x * ROWS;
+    const bf16_t* __restrict__ W = static_cast<const bf16_t*>(a.W);
+    const bf16_t* __restrict__ X = static_cast<const bf16_t*>(a.xb);
+    const int K = a.K, nblk = K / 64;  // K is a multiple of 64 on this path
+
+    const bf16_t* wp[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) wp[t] = W + static_cast<size_t>(min(row0 + t * 16 + l16, a.N - 1)) * K + g * 8;
+    const bf16_t* xp = X + static_cast<size_t>(l16 < a.nb ? l16 : 0) * K + g * 8;
+
+    f32x4_d acc[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[t][v] = 0.f;
+
+    for (int kb0 = wave; kb0 < nblk; kb0 += 4 * U) {
+        uint4 wv[U][2][2], xv[U][2];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int kb = kb0 + 4 * u;
+            const int kc = kb < nblk ? kb : kb0;  // past the end: re-read a valid block, zero its activations
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+#pragma unroll
+                for (int t = 0; t < 2; ++t) wv[u][t][j] = *reinterpret_cast<const uint4*>(wp[t] + kc * 64 + j * 32);
+                xv[u][j] = kb < nblk ? *reinterpret_cast<const uint4*>(xp + kc * 64 + j * 32) : make_uint4(0u, 0u, 0u, 0u);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_d, wv[u][t][j]),
+                                                                     __builtin_bit_cast(bf16x8_d, xv[u][j]), acc[t], 0, 0, 0);
+    }
+
+    // D[n][b]: register v of a lane is row 4*g + v of its tile, activation row l16
+    __shared__ float s_red[4][ROWS][16];
+    __shared__ float s_val[ROWS][16];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) s_red[wave][t * 16 + g * 4 + v][l16] = acc[t][v];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int id = tid + 256 * i, r = id >> 4, b = id & 15;
+        s_val[r][b] = (s_red[0][r][b] + s_red[1][r][b]) + (s_red[2][r][b] + s_red[3][r][b]);
+    }
+    __syncthreads();
+
+    if (a.epi == EPI_RESID) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int id = tid + 256 * i, r = id >> 4, b = id & 15, n = row0 + r;
+            if (n < a.N && b < a.nb) {
+                const size_t at = static_cast<size_t>(b) * a.N + n;
+                a.out[at] = a.resid[at] + s_val[r][b];
+            }
+        }
+        return;
+    }
+    // pair epilogues: thread -> (row pair j, activation row b)
+    const int j = tid >> 4, b = tid & 15;
+    const int n0 = row0 + 2 * j;
+    if (n0 >= a.N || b >= a.nb) return;
+    const float v0 = s_val[2 * j][b], v1 = s_val[2 * j + 1][b];
+    if (a.epi == EPI_SWIGLU) {
+        const int F = a.N / 2;
+        static_cast<bf16_t*>(a.out_b)[static_cast<size_t>(b) * F + n0 / 2] = f32_to_bf16(v0 / (1.0f + expf(-v0)) * v1);
+        return;
+    }
+    const int dh = a.kv.dh, nq = a.hq * dh, nk = a.kv.hkv * dh;
+    const int pos = sb.pos[b];
+    const int e = n0 % dh;
+    if (n0 < nq + nk) {
+        const float2 cs = a.rope[static_cast<size_t>(pos) * (dh / 2) + e / 2];
+        const float r0 = v0 * cs.x - v1 * cs.y, r1 = v0 * cs.y + v1 * cs.x;
+        if (n0 < nq) {
+            a.q[static_cast<size_t>(b) * nq + n0] = r0;
+            a.q[static_cast<size_t>(b) * nq + n0 + 1] = r1;
+            return;
+        }
+        const int hk = (n0 - nq) / dh;
+        const int page = a.kv.block_table[sb.seq[b] * a.kv.max_pages + pos / a.kv.page];
+        const size_t at = ((static_cast<size_t>(page) * a.kv.hkv + hk) * a.kv.page + pos % a.kv.page) * dh + e;
+        bf16_t* kp = static_cast<bf16_t*>(a.kv.k);
+        kp[at] = f32_to_bf16(r0);
+        kp[at + 1] = f32_to_bf16(r1);
+        return;
+    }
+    const int hk = (n0 - nq - nk) / dh;
+    const int page = a.kv.block_table[sb.seq[b] * a.kv.max_pages + pos / a.kv.page];
+    const size_t at = ((static_cast<size_t>(page) * a.kv.hkv + hk) * a.kv.page + pos % a.kv.page) * dh + e;
+    bf16_t* vp = static_cast<bf16_t*>(a.kv.v);
+    vp[at] = f32_to_bf16(v0);
+    vp[at + 1] = f32_to_bf16(v1);
+}
+
+void launch_decode_linear_mfma(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
+    const int grid = (a.N + 31) / 32;
+    hipLaunchKernelGGL(decode_linear_mfma_kernel<4>, dim3(grid), dim3(256), 0, st, a, sb);
+}
+
+// ---------------------------------------------------------------------------------------
 // Attention of one new token per sequence over its cached keys/values.
 // Grid (nsplit, nb*hq).  A workgroup takes one slice of the context of one (sequence,
 // query head); TPT = DH/VEC adjacent lanes share a token (one 16-byte load each), and each
@@ -299,9 +425,12 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttn a, SeqBatch
             }
         }
     }
-    float* op = a.o + static_cast<size_t>(b) * a.hq * DH + h * DH;
     if (a.nsplit == 1) {
-        if (tid < DH) op[tid] = O / L;
+        if (tid < DH) {
+            const size_t at = static_cast<size_t>(b) * a.hq * DH + h * DH + tid;
+            if (a.o_dtype == DT_F32) static_cast<float*>(a.o)[at] = O / L;
+            else static_cast<bf16_t*>(a.o)[at] = f32_to_bf16(O / L);
+        }
         return;
     }
     const size_t pbase = static_cast<size_t>(bh) * a.nsplit;
@@ -341,7 +470,9 @@ __global__ __launch_bounds__(DH) void decode_attn_merge_kernel(DecodeAttn a) {
     float ox = 0.f;
 #pragma unroll
     for (int s = 0; s < ATTN_MAX_SPLIT; ++s) ox = fmaf(po[s], s_w[s], ox);
-    a.o[static_cast<size_t>(bh) * DH + tid] = ox / s_L;
+    const size_t at = static_cast<size_t>(bh) * DH + tid;
+    if (a.o_dtype == DT_F32) static_cast<float*>(a.o)[at] = ox / s_L;
+    else static_cast<bf16_t*>(a.o)[at] = f32_to_bf16(ox / s_L);
 }
 
 void launch_decode_attn(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st) {

@@ -44,12 +44,18 @@ struct DecodeLinear {
     int32_t hq;
     KvView kv;
     const float2* rope;    // [max_seq_len, dh/2] (cos, sin)
+    // matrix-core variant (launch_decode_linear_mfma): bf16 weights, 9..16 rows
+    const void* xb;        // [nb, K] bf16 activations (already normalised where needed)
+    void* out_b;           // EPI_SWIGLU output [nb, N/2] bf16
 };
 void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st);
+// same contract with xb/out_b; requires wt == DT_BF16, nb <= 16, K % 64 == 0, gain == null
+void launch_decode_linear_mfma(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st);
 
 struct DecodeAttn {
     const float* q;        // [nb, hq*dh], already rotated
-    float* o;              // [nb, hq*dh]
+    void* o;               // [nb, hq*dh] in o_dtype
+    int32_t o_dtype;
     int32_t nb, hq;
     int32_t kv_dtype;
     KvView kv;

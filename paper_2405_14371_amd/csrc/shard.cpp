@@ -280,10 +280,59 @@ int pick_nsplit(const shard* s, const SeqBatch& sb) {
     return n < 1 ? 1 : n;
 }
 
+// Decode step for 9..16 sequences with bf16 weights: projections on the matrix cores, one
+// pass over the weights for the whole batch.
+void run_decode_mfma(shard* s, const SeqBatch& sb, const float* x_in, float* x_out, hipStream_t st) {
+    const shard_model_cfg& m = s->m;
+    const int B = sb.n;
+    mark_layer(s, 0, st);
+    for (int li = 0; li < s->L; ++li) {
+        const LayerDev& l = s->layers[li];
+        const float* x = li == 0 ? x_in : x_out;
+        const KvView kvv = kv_view(s, li);
+        DecodeLinear d{};
+        d.wt = DT_BF16; d.nb = B; d.hq = m.n_heads; d.kv = kvv; d.rope = s->rope;
+        {
+            Bracket t(s, SHARD_K_DECODE_QKV, st);
+            launch_rmsnorm(x, l.g_attn, m.rms_eps, s->h, DT_BF16, B, m.d_model, st);
+            d.W = l.wqkv; d.N = s->nqkv; d.K = m.d_model; d.xb = s->h; d.epi = EPI_QKV; d.q = s->q;
+            launch_decode_linear_mfma(d, sb, st);
+        }
+        {
+            DecodeAttn a{};
+            a.q = s->q; a.o = s->o; a.o_dtype = DT_BF16; a.nb = B; a.hq = m.n_heads; a.kv_dtype = DT_BF16; a.kv = kvv;
+            a.nsplit = pick_nsplit(s, sb); a.part_o = s->part_o; a.part_ml = s->part_ml;
+            Bracket t(s, SHARD_K_DECODE_ATTN, st);
+            launch_decode_attn(a, sb, st);
+        }
+        {
+            d.W = l.wo; d.N = m.d_model; d.K = s->nq; d.xb = s->o; d.epi = EPI_RESID; d.resid = x; d.out = x_out;
+            Bracket t(s, SHARD_K_DECODE_O, st);
+            launch_decode_linear_mfma(d, sb, st);
+        }
+        {
+            Bracket t(s, SHARD_K_DECODE_GATEUP, st);
+            launch_rmsnorm(x_out, l.g_ffn, m.rms_eps, s->h, DT_BF16, B, m.d_model, st);
+            d.W = l.wgu; d.N = 2 * m.ffn_dim; d.K = m.d_model; d.xb = s->h; d.epi = EPI_SWIGLU; d.out_b = s->f;
+            launch_decode_linear_mfma(d, sb, st);
+        }
+        {
+            d.W = l.wd; d.N = m.d_model; d.K = m.ffn_dim; d.xb = s->f; d.epi = EPI_RESID; d.resid = x_out; d.out = x_out;
+            Bracket t(s, SHARD_K_DECODE_DOWN, st);
+            launch_decode_linear_mfma(d, sb, st);
+        }
+        mark_layer(s, li + 1, st);
+    }
+}
+
 void run_decode(shard* s, const SeqBatch& sb, const float* x_in, float* x_out, hipStream_t st) {
     const shard_model_cfg& m = s->m;
     const int dt = m.weight_dtype == SHARD_F32 ? DT_F32 : DT_BF16;
     const int B = sb.n;
+    if (dt == DT_BF16 && B > 8 && B <= 16 && m.d_model % 64 == 0 && m.ffn_dim % 64 == 0 && s->nq % 64 == 0) {
+        run_decode_mfma(s, sb, x_in, x_out, st);
+        return;
+    }
     float* o = static_cast<float*>(s->o);
     float* f = static_cast<float*>(s->f);
     mark_layer(s, 0, st);
@@ -306,7 +355,7 @@ void run_decode(shard* s, const SeqBatch& sb, const float* x_in, float* x_out, h
         }
         {
             DecodeAttn a{};
-            a.q = s->q; a.o = o; a.nb = B; a.hq = m.n_heads; a.kv_dtype = dt; a.kv = kvv;
+            a.q = s->q; a.o = o; a.o_dtype = DT_F32; a.nb = B; a.hq = m.n_heads; a.kv_dtype = dt; a.kv = kvv;
             a.nsplit = pick_nsplit(s, sb); a.part_o = s->part_o; a.part_ml = s->part_ml;
             Bracket t(s, SHARD_K_DECODE_ATTN, st);
             launch_decode_attn(a, sb, st);

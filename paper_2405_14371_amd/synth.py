@@ -71,14 +71,20 @@ def bf16_bits(a: np.ndarray) -> np.ndarray:
 
 
 def layer_weights(cfg: dict, seed: int, layer: int, dtype: str = "f32") -> dict:
-    """All tensors of decoder layer `layer` as float32 arrays (bf16-rounded if dtype='bf16')."""
+    """All tensors of decoder layer `layer` as float32 arrays (bf16-rounded if dtype='bf16').
+    Each matrix has its own stream, so they are drawn concurrently (numpy releases the GIL)."""
     if dtype not in ("f32", "bf16"):
         raise ValueError(dtype)
-    out = {}
-    for idx, (name, shape) in enumerate(weight_shapes(cfg).items()):
+    from concurrent.futures import ThreadPoolExecutor
+
+    def draw(item):
+        idx, (name, shape) = item
         w = _stream(seed, 1, layer, idx).standard_normal(shape, dtype=np.float32)
         w *= np.float32(WEIGHT_STD)
-        out[name] = round_to_bf16(w) if dtype == "bf16" else w
+        return name, (round_to_bf16(w) if dtype == "bf16" else w)
+
+    with ThreadPoolExecutor(max_workers=7) as pool:
+        out = dict(pool.map(draw, enumerate(weight_shapes(cfg).items())))
     for name in GAIN_NAMES:
         out[name] = np.ones(cfg["d_model"], dtype=np.float32)
     return out

@@ -20,7 +20,7 @@ pytestmark = pytest.mark.gpu
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 
-def run_fullsize(lib, name, seqs_on_gpu, page_size=16):
+def run_fullsize(lib, name, seqs_on_gpu, page_size=16, batched=True):
     path = os.path.join(GOLDEN, f"{name}.npz")
     if not os.path.exists(path):
         pytest.skip(f"{path} not generated")
@@ -48,16 +48,23 @@ def run_fullsize(lib, name, seqs_on_gpu, page_size=16):
     assert wsum == pytest.approx(float(gold["weight_checksum"]), rel=1e-12), "weight generator drifted"
     B = len(seqs_on_gpu)
     sh = lib.Shard(cfg, layers, 0, weight_dtype=wd, max_seqs=B, max_seq_len=T + n_dec, page_size=page_size,
-                   max_batch_tokens=B * T)
+                   max_batch_tokens=(B if batched else 1) * T)
     del layers
     ids = [sh.seq_alloc() for _ in range(B)]
     st = torch.cuda.current_stream().cuda_stream
     xp = torch.from_numpy(np.stack([xs[s][0] for s in seqs_on_gpu])).cuda()           # [B, T, d]
     xd = torch.from_numpy(np.stack([xs[s][1] for s in seqs_on_gpu], axis=1)).cuda()   # [n_dec, B, d]
     yp, yd = torch.empty_like(xp), torch.empty_like(xd)
-    sh.prefill(ids, T, xp, yp, st)
-    for s in range(n_dec):
-        sh.decode(ids, xd[s], yd[s], st)
+    if batched:            # one call carries all sequences
+        sh.prefill(ids, T, xp, yp, st)
+        for s in range(n_dec):
+            sh.decode(ids, xd[s], yd[s], st)
+    else:                  # micro-batches of one sequence each, round-robin through the shard
+        for b in range(B):
+            sh.prefill([ids[b]], T, xp[b], yp[b], st)
+        for s in range(n_dec):
+            for b in range(B):
+                sh.decode([ids[b]], xd[s, b], yd[s, b], st)
     torch.cuda.synchronize()
     yp, yd = yp.cpu().numpy().astype(np.float64), yd.cpu().numpy().astype(np.float64)
     sh.close()
@@ -85,3 +92,17 @@ def test_config2_llama2_7b_layers_0_7_fp32_512_plus_128(lib):
 def test_config3_llama2_7b_32_layers_bf16_1024_plus_256(lib):
     """The whole 7B stack as one shard, bf16 weights and cache, batch 1, 1024 + 256."""
     run_fullsize(lib, "c3", [0])
+
+
+def test_config4_llama2_13b_layers_0_19_bf16_eight_microbatches(lib):
+    """13B shape, 20 layers, bf16: eight micro-batches of one sequence each, 256-token prefill
+    and 128 decode steps, driven round-robin (the order one pipeline stage sees, Sec. 4.2
+    "Pipeline Execution Optimization").  The oracle ran micro-batches 0 and 7."""
+    run_fullsize(lib, "c4", list(range(8)), batched=False)
+
+
+def test_config5_llama2_70b_layers_0_19_gqa_bf16_batch16(lib):
+    """70B shape (64 query / 8 KV heads), 20 layers, bf16, batch 16, 512 + 128, 16-token
+    pages.  The oracle ran sequences 0 and 15 (batch independence is one of its pins); the
+    other fourteen are checked for finiteness."""
+    run_fullsize(lib, "c5", list(range(16)))
