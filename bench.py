@@ -36,6 +36,8 @@ WORKLOADS = {
     # name: model, layers, dtype, batch, prefill tokens, decode steps
     "llama2-7b-l0-7-fp32-b1-p512-d128": dict(model="7b", layers=8, dtype="f32", B=1, T=512, n_dec=128),
     "llama2-7b-32l-bf16-b1-p1024-d256": dict(model="7b", layers=32, dtype="bf16", B=1, T=1024, n_dec=256),
+    "llama2-13b-l0-19-bf16-8xb1-p256-d128": dict(model="13b", layers=20, dtype="bf16", B=1, T=256, n_dec=128, micro=8),
+    "llama2-70b-l0-19-bf16-b16-p512-d128": dict(model="70b", layers=20, dtype="bf16", B=16, T=512, n_dec=128),
     "tiny-2l-fp32-b1-p32-d16": dict(model="tiny", layers=2, dtype="f32", B=1, T=32, n_dec=16),
 }
 DEFAULT_WORKLOAD = "llama2-7b-l0-7-fp32-b1-p512-d128"
@@ -114,17 +116,19 @@ def main():
     work = algorithmic_work(cfg, wl)
     wd = lib.SHARD_F32 if wl["dtype"] == "f32" else lib.SHARD_BF16
     B, T, n_dec, L = wl["B"], wl["T"], wl["n_dec"], wl["layers"]
+    MB = wl.get("micro", 1)     # micro-batches driven round-robin through the shard (each of batch B)
 
     t0 = time.perf_counter()
-    layers = synth.shard_weights(cfg, args.seed, 0, L, wl["dtype"])
-    sh = lib.Shard(cfg, lib.pack_layers(layers, wd), 0, weight_dtype=wd, max_seqs=B, max_seq_len=T + n_dec,
+    layers = [lib.pack_layers([synth.layer_weights(cfg, args.seed, li, wl["dtype"])], wd)[0] for li in range(L)]
+    sh = lib.Shard(cfg, layers, 0, weight_dtype=wd, max_seqs=B * MB, max_seq_len=T + n_dec,
                    page_size=16, max_batch_tokens=B * T)
     del layers
-    x_pre = torch.from_numpy(np.concatenate(
-        [synth.hidden_states(cfg, args.seed, "prefill", 0, b, 1, T) for b in range(B)])).cuda()
-    x_dec = torch.from_numpy(np.stack(
-        [np.concatenate([synth.hidden_states(cfg, args.seed, "dec", s, b, 1, 1) for b in range(B)])
-         for s in range(n_dec)])).cuda()                      # [n_dec, B, 1, d]
+    x_pre = torch.from_numpy(np.stack([np.concatenate(
+        [synth.hidden_states(cfg, args.seed, "prefill", 0, mb * B + b, 1, T) for b in range(B)])
+        for mb in range(MB)])).cuda()                         # [MB, B, T, d]
+    x_dec = torch.from_numpy(np.stack([np.stack(
+        [np.concatenate([synth.hidden_states(cfg, args.seed, "dec", s, mb * B + b, 1, 1) for b in range(B)])
+         for mb in range(MB)]) for s in range(n_dec)])).cuda()   # [n_dec, MB, B, 1, d]
     y_pre = torch.empty_like(x_pre)
     y_dec = torch.empty_like(x_dec)
     setup_s = time.perf_counter() - t0
@@ -134,17 +138,20 @@ def main():
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
     def one_step(timed):
-        ids = [sh.seq_alloc() for _ in range(B)]
+        ids = [[sh.seq_alloc() for _ in range(B)] for _ in range(MB)]
         e0, e1, e2 = ev(), ev(), ev()
         e0.record(stream)
-        sh.prefill(ids, T, x_pre, y_pre, st)
+        for mb in range(MB):
+            sh.prefill(ids[mb], T, x_pre[mb], y_pre[mb], st)
         e1.record(stream)
         for s in range(n_dec):
-            sh.decode(ids, x_dec[s], y_dec[s], st)
+            for mb in range(MB):
+                sh.decode(ids[mb], x_dec[s, mb], y_dec[s, mb], st)
         e2.record(stream)
         torch.cuda.synchronize()
-        for i in ids:
-            sh.seq_free(i)
+        for group in ids:
+            for i in group:
+                sh.seq_free(i)
         return (e0.elapsed_time(e1) * 1e-3, e1.elapsed_time(e2) * 1e-3) if timed else None
 
     for _ in range(args.warmup):
@@ -158,9 +165,9 @@ def main():
 
     t_pre = sum(t[0] for t in times)
     t_dec = sum(t[1] for t in times)
-    dec_tok_s = B * n_dec * args.steps / t_dec
-    dec_gbps = work["decode_bytes"] * n_dec * args.steps / t_dec / 1e9
-    pre_tflops = work["prefill_flops"] * args.steps / t_pre / 1e12
+    dec_tok_s = MB * B * n_dec * args.steps / t_dec
+    dec_gbps = work["decode_bytes"] * MB * n_dec * args.steps / t_dec / 1e9
+    pre_tflops = work["prefill_flops"] * MB * args.steps / t_pre / 1e12
 
     # one more step with HIP events around every launch, for the per-kernel roofline
     sh.timing_enable(True)
@@ -169,7 +176,7 @@ def main():
     sh.timing_enable(False)
     proj = ("qkv", "o", "gateup", "down")
     lin = {f: sum(kt["decode_" + k][f] for k in proj) for f in ("launches", "seconds")}
-    lin_bytes = sum(work["linear_bytes"].values()) * L * n_dec
+    lin_bytes = sum(work["linear_bytes"].values()) * L * n_dec * MB
     lin_gbps = lin_bytes / lin["seconds"] / 1e9
     # HBM bytes per launch from rocprofv3 PMC runs of this same command (FETCH_SIZE and
     # WRITE_SIZE, scaled by what they read for a copy of known size); see profiles/
@@ -187,7 +194,7 @@ def main():
         "algorithmic_bytes_per_launch": round(lin_bytes / max(1, lin["launches"])),
     }
     gm = {f: sum(kt["prefill_" + k][f] for k in proj) for f in ("launches", "seconds")}
-    gm_flops = sum(work["gemm_flops"].values()) * L
+    gm_flops = sum(work["gemm_flops"].values()) * L * MB
     peak_tf = MFMA_PEAK_TFLOPS[wl["dtype"]]
     roofline_prefill = {
         "kernel": "gemm_kernel (MFMA projections of shard_prefill)",
@@ -209,12 +216,12 @@ def main():
         "value": round(dec_tok_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round((t_pre + t_dec) / args.steps * 1e3, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": wl["dtype"], "data": "synthetic",
-        "config": {"workload": args.workload, "layers": L, "batch": B, "prefill_tokens": T, "decode_steps": n_dec,
-                   "page_size": 16, "seed": args.seed},
-        "decode_ms_per_token": round(t_dec / (n_dec * args.steps) * 1e3, 4),
+        "config": {"workload": args.workload, "layers": L, "batch": B, "micro_batches": MB, "prefill_tokens": T,
+                   "decode_steps": n_dec, "page_size": 16, "seed": args.seed},
+        "decode_ms_per_step": round(t_dec / (n_dec * MB * args.steps) * 1e3, 4),
         "decode_gbps": round(dec_gbps, 1), "decode_hbm_frac": round(dec_gbps / HBM_PEAK_GBPS, 4),
         "prefill_ms": round(t_pre / args.steps * 1e3, 3),
-        "prefill_tokens_per_s": round(B * T * args.steps / t_pre, 1),
+        "prefill_tokens_per_s": round(MB * B * T * args.steps / t_pre, 1),
         "prefill_tflops": round(pre_tflops, 2), "prefill_mfma_frac": round(pre_tflops / peak_tf, 4),
         "roofline": roofline, "roofline_prefill": roofline_prefill, "kernel_ms_instrumented_step": kernel_seconds,
         "wall_s_timed_region": round(wall, 3), "setup_s": round(setup_s, 1),

@@ -60,7 +60,10 @@ typedef struct {
     int32_t ffn_dim;      /* SwiGLU inner width F */
     float rms_eps;
     float rope_theta;
-    int32_t weight_dtype; /* SHARD_F32 or SHARD_BF16: dtype of the matrices AND of the KV cache */
+    int32_t weight_dtype; /* dtype of the matrices.  SHARD_F32: KV cache and all arithmetic fp32.
+                             SHARD_BF16: fp32 accumulation and residual stream; the KV cache and the
+                             activations fed to the matrix cores are IEEE half (same 2 bytes per
+                             element as bf16, 8x finer rounding; bf16 weights convert to it exactly) */
     int32_t act_dtype;    /* dtype of x_in / x_out at the boundary; only SHARD_F32 is supported:
                              the paper runs full precision, and an fp32 hand-off keeps shard
                              composition exact.  The residual stream inside is always fp32. */

@@ -158,18 +158,20 @@ __global__ __launch_bounds__(256) void decode_linear_kernel(DecodeLinear a, SeqB
         const int hk = (n0 - nq) / dh;
         const int page = a.kv.block_table[sb.seq[b] * a.kv.max_pages + pos / a.kv.page];
         const size_t at = ((static_cast<size_t>(page) * a.kv.hkv + hk) * a.kv.page + pos % a.kv.page) * dh + e;
-        WT* kp = static_cast<WT*>(a.kv.k);
-        kp[at] = Elem<WT>::from_f32(r0);
-        kp[at + 1] = Elem<WT>::from_f32(r1);
+        typedef typename ActOf<WT>::type CT;  // cache element type
+        CT* kp = static_cast<CT*>(a.kv.k);
+        kp[at] = Elem<CT>::from_f32(r0);
+        kp[at + 1] = Elem<CT>::from_f32(r1);
         return;
     }
     {
+        typedef typename ActOf<WT>::type CT;
         const int hk = (n0 - nq - nk) / dh, e = n0 % dh;
         const int page = a.kv.block_table[sb.seq[b] * a.kv.max_pages + pos / a.kv.page];
         const size_t at = ((static_cast<size_t>(page) * a.kv.hkv + hk) * a.kv.page + pos % a.kv.page) * dh + e;
-        WT* vp = static_cast<WT*>(a.kv.v);
-        vp[at] = Elem<WT>::from_f32(v0);
-        vp[at + 1] = Elem<WT>::from_f32(v1);
+        CT* vp = static_cast<CT*>(a.kv.v);
+        vp[at] = Elem<CT>::from_f32(v0);
+        vp[at + 1] = Elem<CT>::from_f32(v1);
     }
 }
 
@@ -209,9 +211,9 @@ void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t
 // in interleaved 64-element blocks and meet in LDS (fixed order).  Lane (row = lane%16,
 // g = lane/16) supplies elements 32*j + 8*g + (0..7) of a block to MFMA j on both operands,
 // so every load instruction reads 64 contiguous bytes per row.  Activations arrive already
-// rounded to bf16 (and normalised where the step needs it).
+// rounded to half (and normalised where the step needs it).
 // ---------------------------------------------------------------------------------------
-typedef __bf16 bf16x8_d __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8_d __attribute__((ext_vector_type(8)));
 typedef float f32x4_d __attribute__((ext_vector_type(4)));
 
 template <int U>
@@ -221,13 +223,13 @@ __global__ __launch_bounds__(256) void decode_linear_mfma_kernel(DecodeLinear a,
     const int l16 = lane & 15, g = lane >> 4;
     const int row0 = blockIdx.x * ROWS;
     const bf16_t* __restrict__ W = static_cast<const bf16_t*>(a.W);
-    const bf16_t* __restrict__ X = static_cast<const bf16_t*>(a.xb);
+    const f16_t* __restrict__ X = static_cast<const f16_t*>(a.xb);
     const int K = a.K, nblk = K / 64;  // K is a multiple of 64 on this path
 
     const bf16_t* wp[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) wp[t] = W + static_cast<size_t>(min(row0 + t * 16 + l16, a.N - 1)) * K + g * 8;
-    const bf16_t* xp = X + static_cast<size_t>(l16 < a.nb ? l16 : 0) * K + g * 8;
+    const f16_t* xp = X + static_cast<size_t>(l16 < a.nb ? l16 : 0) * K + g * 8;
 
     f32x4_d acc[2];
 #pragma unroll
@@ -254,8 +256,9 @@ __global__ __launch_bounds__(256) void decode_linear_mfma_kernel(DecodeLinear a,
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int t = 0; t < 2; ++t)
-                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_d, wv[u][t][j]),
-                                                                     __builtin_bit_cast(bf16x8_d, xv[u][j]), acc[t], 0, 0, 0);
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                        __builtin_bit_cast(f16x8_d, bf16x8_to_f16x8(wv[u][t][j])),
+                        __builtin_bit_cast(f16x8_d, xv[u][j]), acc[t], 0, 0, 0);
     }
 
     // D[n][b]: register v of a lane is row 4*g + v of its tile, activation row l16
@@ -291,7 +294,7 @@ __global__ __launch_bounds__(256) void decode_linear_mfma_kernel(DecodeLinear a,
     const float v0 = s_val[2 * j][b], v1 = s_val[2 * j + 1][b];
     if (a.epi == EPI_SWIGLU) {
         const int F = a.N / 2;
-        static_cast<bf16_t*>(a.out_b)[static_cast<size_t>(b) * F + n0 / 2] = f32_to_bf16(v0 / (1.0f + expf(-v0)) * v1);
+        static_cast<f16_t*>(a.out_b)[static_cast<size_t>(b) * F + n0 / 2] = static_cast<f16_t>(v0 / (1.0f + expf(-v0)) * v1);
         return;
     }
     const int dh = a.kv.dh, nq = a.hq * dh, nk = a.kv.hkv * dh;
@@ -308,17 +311,17 @@ __global__ __launch_bounds__(256) void decode_linear_mfma_kernel(DecodeLinear a,
         const int hk = (n0 - nq) / dh;
         const int page = a.kv.block_table[sb.seq[b] * a.kv.max_pages + pos / a.kv.page];
         const size_t at = ((static_cast<size_t>(page) * a.kv.hkv + hk) * a.kv.page + pos % a.kv.page) * dh + e;
-        bf16_t* kp = static_cast<bf16_t*>(a.kv.k);
-        kp[at] = f32_to_bf16(r0);
-        kp[at + 1] = f32_to_bf16(r1);
+        f16_t* kp = static_cast<f16_t*>(a.kv.k);
+        kp[at] = static_cast<f16_t>(r0);
+        kp[at + 1] = static_cast<f16_t>(r1);
         return;
     }
     const int hk = (n0 - nq - nk) / dh;
     const int page = a.kv.block_table[sb.seq[b] * a.kv.max_pages + pos / a.kv.page];
     const size_t at = ((static_cast<size_t>(page) * a.kv.hkv + hk) * a.kv.page + pos % a.kv.page) * dh + e;
-    bf16_t* vp = static_cast<bf16_t*>(a.kv.v);
-    vp[at] = f32_to_bf16(v0);
-    vp[at + 1] = f32_to_bf16(v1);
+    f16_t* vp = static_cast<f16_t*>(a.kv.v);
+    vp[at] = static_cast<f16_t>(v0);
+    vp[at + 1] = static_cast<f16_t>(v1);
 }
 
 void launch_decode_linear_mfma(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
@@ -429,7 +432,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttn a, SeqBatch
         if (tid < DH) {
             const size_t at = static_cast<size_t>(b) * a.hq * DH + h * DH + tid;
             if (a.o_dtype == DT_F32) static_cast<float*>(a.o)[at] = O / L;
-            else static_cast<bf16_t*>(a.o)[at] = f32_to_bf16(O / L);
+            else static_cast<f16_t*>(a.o)[at] = static_cast<f16_t>(O / L);
         }
         return;
     }
@@ -472,7 +475,7 @@ __global__ __launch_bounds__(DH) void decode_attn_merge_kernel(DecodeAttn a) {
     for (int s = 0; s < ATTN_MAX_SPLIT; ++s) ox = fmaf(po[s], s_w[s], ox);
     const size_t at = static_cast<size_t>(bh) * DH + tid;
     if (a.o_dtype == DT_F32) static_cast<float*>(a.o)[at] = ox / s_L;
-    else static_cast<bf16_t*>(a.o)[at] = f32_to_bf16(ox / s_L);
+    else static_cast<f16_t*>(a.o)[at] = static_cast<f16_t>(ox / s_L);
 }
 
 void launch_decode_attn(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st) {
@@ -482,17 +485,17 @@ void launch_decode_attn(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st)
     switch (a.kv.dh) {
         case 32:
             if (f32) hipLaunchKernelGGL((decode_attn_kernel<float, 32, 4>), grid, block, 0, st, a, sb);
-            else hipLaunchKernelGGL((decode_attn_kernel<bf16_t, 32, 4>), grid, block, 0, st, a, sb);
+            else hipLaunchKernelGGL((decode_attn_kernel<f16_t, 32, 4>), grid, block, 0, st, a, sb);
             if (a.nsplit > 1) hipLaunchKernelGGL(decode_attn_merge_kernel<32>, dim3(units), dim3(32), 0, st, a);
             break;
         case 64:
             if (f32) hipLaunchKernelGGL((decode_attn_kernel<float, 64, 4>), grid, block, 0, st, a, sb);
-            else hipLaunchKernelGGL((decode_attn_kernel<bf16_t, 64, 4>), grid, block, 0, st, a, sb);
+            else hipLaunchKernelGGL((decode_attn_kernel<f16_t, 64, 4>), grid, block, 0, st, a, sb);
             if (a.nsplit > 1) hipLaunchKernelGGL(decode_attn_merge_kernel<64>, dim3(units), dim3(64), 0, st, a);
             break;
         default:
             if (f32) hipLaunchKernelGGL((decode_attn_kernel<float, 128, 4>), grid, block, 0, st, a, sb);
-            else hipLaunchKernelGGL((decode_attn_kernel<bf16_t, 128, 4>), grid, block, 0, st, a, sb);
+            else hipLaunchKernelGGL((decode_attn_kernel<f16_t, 128, 4>), grid, block, 0, st, a, sb);
             if (a.nsplit > 1) hipLaunchKernelGGL(decode_attn_merge_kernel<128>, dim3(units), dim3(128), 0, st, a);
             break;
     }

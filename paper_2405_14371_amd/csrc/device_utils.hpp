@@ -6,7 +6,8 @@
 
 namespace shk {
 
-typedef uint16_t bf16_t;  // raw bf16 bit pattern
+typedef uint16_t bf16_t;  // raw bf16 bit pattern (weights as the caller supplies them)
+typedef _Float16 f16_t;   // IEEE half: the 16-bit format of activations and of the KV cache
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -33,6 +34,33 @@ template <> struct Elem<bf16_t> {
     __device__ static __forceinline__ bf16_t from_f32(float v) { return f32_to_bf16(v); }
 };
 
+template <> struct Elem<f16_t> {
+    static constexpr int VEC = 8;
+    __device__ static __forceinline__ float to_f32(f16_t v) { return static_cast<float>(v); }
+    __device__ static __forceinline__ f16_t from_f32(float v) { return static_cast<f16_t>(v); }
+};
+
+// 16-bit format that goes with a weight type: activations fed to the matrix cores and the
+// KV cache.  bf16 weights pair with IEEE half: its 11-bit significand keeps the rounding
+// of activations 8x smaller than bf16 would, and every bf16 weight in half's normal range
+// converts to half exactly (8-bit significand).
+template <typename WT> struct ActOf;
+template <> struct ActOf<float> { typedef float type; };
+template <> struct ActOf<bf16_t> { typedef f16_t type; };
+
+// 8 bf16 (16 bytes) -> 8 half (16 bytes); exact for values in half's normal range
+__device__ __forceinline__ uint4 bf16x8_to_f16x8(const uint4& w) {
+    typedef __fp16 h2 __attribute__((ext_vector_type(2)));
+    const uint32_t in[4] = {w.x, w.y, w.z, w.w};
+    uint32_t out[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const h2 p = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(in[i] << 16), __uint_as_float(in[i] & 0xFFFF0000u));
+        out[i] = __builtin_bit_cast(uint32_t, p);
+    }
+    return make_uint4(out[0], out[1], out[2], out[3]);
+}
+
 // Load 16 bytes at p (16-byte aligned) and widen to fp32: 4 floats or 8 bf16.
 template <typename T> struct Vec16;
 template <> struct Vec16<float> {
@@ -53,6 +81,20 @@ template <> struct Vec16<bf16_t> {
             v[2 * i] = __uint_as_float(w[i] << 16);
             v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
         }
+    }
+    __device__ __forceinline__ void zero() {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = 0.f;
+    }
+};
+
+template <> struct Vec16<f16_t> {
+    float v[8];
+    __device__ __forceinline__ void load(const f16_t* p) {
+        typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+        const h8 t = *reinterpret_cast<const h8*>(p);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = static_cast<float>(t[i]);
     }
     __device__ __forceinline__ void zero() {
 #pragma unroll

@@ -8,7 +8,7 @@
 
 namespace shk {
 
-enum DType { DT_F32 = 0, DT_BF16 = 1 };
+enum DType { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };  // bf16: weights only; f16: activations and KV cache
 
 // One layer's paged KV cache.  Element (page p, kv head h, slot s, e) of K or V lives at
 // ((p * hkv + h) * page + s) * dh + e; token u of sequence q is in page
@@ -45,8 +45,8 @@ struct DecodeLinear {
     KvView kv;
     const float2* rope;    // [max_seq_len, dh/2] (cos, sin)
     // matrix-core variant (launch_decode_linear_mfma): bf16 weights, 9..16 rows
-    const void* xb;        // [nb, K] bf16 activations (already normalised where needed)
-    void* out_b;           // EPI_SWIGLU output [nb, N/2] bf16
+    const void* xb;        // [nb, K] half activations (already normalised where needed)
+    void* out_b;           // EPI_SWIGLU output [nb, N/2] half
 };
 void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st);
 // same contract with xb/out_b; requires wt == DT_BF16, nb <= 16, K % 64 == 0, gain == null

@@ -41,7 +41,7 @@ void launch_rmsnorm(const float* x, const float* gain, float eps, void* out, int
     if (out_dtype == DT_F32)
         hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(M), dim3(256), 0, st, x, gain, eps, static_cast<float*>(out), d);
     else
-        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(M), dim3(256), 0, st, x, gain, eps, static_cast<bf16_t*>(out), d);
+        hipLaunchKernelGGL(rmsnorm_kernel<f16_t>, dim3(M), dim3(256), 0, st, x, gain, eps, static_cast<f16_t*>(out), d);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -98,8 +98,9 @@ __device__ __forceinline__ void gemm_epilogue(const PrefillGemm& a, const SeqBat
 }
 
 // ---------------------------------------------------------------------------------------
-// GEMM on the matrix cores: v_mfma_f32_32x32x2_f32 for fp32 operands,
-// v_mfma_f32_32x32x16_bf16 for bf16 operands, fp32 accumulation in both.
+// GEMM on the matrix cores, fp32 accumulation: v_mfma_f32_32x32x2_f32 for fp32 weights and
+// activations; for bf16 weights the activations are IEEE half, the weight tile is converted
+// to half (exactly) on its way into LDS, and the product runs on v_mfma_f32_32x32x16_f16.
 // Workgroup tile BN (features) x BM (rows), four waves in a 2x2 arrangement, each owning
 // (BN/2) x (BM/2) as 32x32 MFMA tiles.  K is walked in steps of 64 bytes per row (16 fp32
 // or 32 bf16) through two LDS stages: the global loads of step k+1 are in flight while
@@ -112,7 +113,7 @@ __device__ __forceinline__ void gemm_epilogue(const PrefillGemm& a, const SeqBat
 constexpr int GEMM_ROW_DW = 16;   // dwords of k per row per step
 constexpr int GEMM_PITCH = 20;    // LDS row pitch in dwords
 
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 
 template <typename T>
 __device__ __forceinline__ void mfma_chunk(const float4& w, const float4& x, f32x16& acc);
@@ -125,8 +126,8 @@ __device__ __forceinline__ void mfma_chunk<float>(const float4& w, const float4&
 }
 template <>
 __device__ __forceinline__ void mfma_chunk<bf16_t>(const float4& w, const float4& x, f32x16& acc) {
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, w), __builtin_bit_cast(bf16x8_t, x),
-                                                  acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, w), __builtin_bit_cast(f16x8_t, x),
+                                                 acc, 0, 0, 0);
 }
 
 template <typename T, int BN, int BM>
@@ -148,8 +149,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(PrefillGemm a, SeqBatch sb, i
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wn = wave >> 1, wm = wave & 1;
     const int l32 = lane & 31, half = lane >> 5;
+    typedef typename ActOf<T>::type AT;  // activation type (same size as T)
     const T* __restrict__ W = static_cast<const T*>(a.W);
-    const T* __restrict__ X = static_cast<const T*>(a.A);
+    const AT* __restrict__ X = static_cast<const AT*>(a.A);
 
     f32x16 acc[TN][TM];
 #pragma unroll
@@ -167,6 +169,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(PrefillGemm a, SeqBatch sb, i
             const bool ok = (n0 + row < a.N) && (k < a.K);
             gw[i] = ok ? *reinterpret_cast<const float4*>(W + static_cast<size_t>(n0 + row) * a.K + k)
                        : make_float4(0.f, 0.f, 0.f, 0.f);
+            if constexpr (sizeof(T) == 2)  // bf16 weights meet half activations: convert the tile once
+                gw[i] = __builtin_bit_cast(float4, bf16x8_to_f16x8(__builtin_bit_cast(uint4, gw[i])));
         }
 #pragma unroll
         for (int i = 0; i < LX; ++i) {
@@ -226,7 +230,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(PrefillGemm a, SeqBatch sb, i
                 const int n4 = n0 + wn * (BN / 2) + i * 32 + vq * 8 + half * 4;
                 const int m = m0 + wm * (BM / 2) + j * 32 + l32;
                 const float val[4] = {acc[i][j][vq * 4], acc[i][j][vq * 4 + 1], acc[i][j][vq * 4 + 2], acc[i][j][vq * 4 + 3]};
-                gemm_epilogue<T>(a, sb, m, n4, val);
+                gemm_epilogue<AT>(a, sb, m, n4, val);
             }
 }
 
@@ -265,10 +269,10 @@ __device__ __forceinline__ float4 load4(const KT* p);
 template <>
 __device__ __forceinline__ float4 load4<float>(const float* p) { return *reinterpret_cast<const float4*>(p); }
 template <>
-__device__ __forceinline__ float4 load4<bf16_t>(const bf16_t* p) {
-    const uint2 t = *reinterpret_cast<const uint2*>(p);
-    return make_float4(__uint_as_float(t.x << 16), __uint_as_float(t.x & 0xFFFF0000u),
-                       __uint_as_float(t.y << 16), __uint_as_float(t.y & 0xFFFF0000u));
+__device__ __forceinline__ float4 load4<f16_t>(const f16_t* p) {
+    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+    const h4 t = *reinterpret_cast<const h4*>(p);
+    return make_float4(static_cast<float>(t[0]), static_cast<float>(t[1]), static_cast<float>(t[2]), static_cast<float>(t[3]));
 }
 
 template <typename KT, typename OT, int DH>
@@ -386,10 +390,10 @@ static void launch_pa(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st) 
 void launch_prefill_attn(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st) {
     if (a.kv_dtype == DT_F32) {
         if (a.out_dtype == DT_F32) launch_pa<float, float>(a, sb, st);
-        else launch_pa<float, bf16_t>(a, sb, st);
+        else launch_pa<float, f16_t>(a, sb, st);
     } else {
-        if (a.out_dtype == DT_F32) launch_pa<bf16_t, float>(a, sb, st);
-        else launch_pa<bf16_t, bf16_t>(a, sb, st);
+        if (a.out_dtype == DT_F32) launch_pa<f16_t, float>(a, sb, st);
+        else launch_pa<f16_t, f16_t>(a, sb, st);
     }
 }
 

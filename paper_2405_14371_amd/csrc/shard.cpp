@@ -220,14 +220,15 @@ void mark_layer(shard* s, int i, hipStream_t st) {
 void run_prefill(shard* s, const SeqBatch& sb, int T, const float* x_in, float* x_out, hipStream_t st) {
     const shard_model_cfg& m = s->m;
     const int M = sb.n * T;
-    const int dt = m.weight_dtype == SHARD_F32 ? DT_F32 : DT_BF16;
+    const int dt = m.weight_dtype == SHARD_F32 ? DT_F32 : DT_BF16;   // weights
+    const int adt = m.weight_dtype == SHARD_F32 ? DT_F32 : DT_F16;   // activations and KV cache
     mark_layer(s, 0, st);
     for (int li = 0; li < s->L; ++li) {
         const LayerDev& l = s->layers[li];
         const float* x = li == 0 ? x_in : x_out;
         {
             Bracket t(s, SHARD_K_PREFILL_NORM, st);
-            launch_rmsnorm(x, l.g_attn, m.rms_eps, s->h, dt, M, m.d_model, st);
+            launch_rmsnorm(x, l.g_attn, m.rms_eps, s->h, adt, M, m.d_model, st);
         }
         PrefillGemm g{};
         g.M = M; g.dt = dt; g.T = T; g.hq = m.n_heads; g.kv = kv_view(s, li); g.rope = s->rope;
@@ -237,8 +238,8 @@ void run_prefill(shard* s, const SeqBatch& sb, int T, const float* x_in, float* 
             launch_prefill_gemm(g, sb, st);
         }
         PrefillAttn at{};
-        at.q = s->q; at.o = s->o; at.out_dtype = dt; at.B = sb.n; at.T = T; at.hq = m.n_heads;
-        at.kv_dtype = dt; at.kv = g.kv;
+        at.q = s->q; at.o = s->o; at.out_dtype = adt; at.B = sb.n; at.T = T; at.hq = m.n_heads;
+        at.kv_dtype = adt; at.kv = g.kv;
         {
             Bracket t(s, SHARD_K_PREFILL_ATTN, st);
             launch_prefill_attn(at, sb, st);
@@ -250,7 +251,7 @@ void run_prefill(shard* s, const SeqBatch& sb, int T, const float* x_in, float* 
         }
         {
             Bracket t(s, SHARD_K_PREFILL_NORM, st);
-            launch_rmsnorm(x_out, l.g_ffn, m.rms_eps, s->h, dt, M, m.d_model, st);
+            launch_rmsnorm(x_out, l.g_ffn, m.rms_eps, s->h, adt, M, m.d_model, st);
         }
         g.A = s->h; g.W = l.wgu; g.N = 2 * m.ffn_dim; g.K = m.d_model; g.epi = EPI_SWIGLU; g.out_act = s->f;
         {
@@ -294,13 +295,13 @@ void run_decode_mfma(shard* s, const SeqBatch& sb, const float* x_in, float* x_o
         d.wt = DT_BF16; d.nb = B; d.hq = m.n_heads; d.kv = kvv; d.rope = s->rope;
         {
             Bracket t(s, SHARD_K_DECODE_QKV, st);
-            launch_rmsnorm(x, l.g_attn, m.rms_eps, s->h, DT_BF16, B, m.d_model, st);
+            launch_rmsnorm(x, l.g_attn, m.rms_eps, s->h, DT_F16, B, m.d_model, st);
             d.W = l.wqkv; d.N = s->nqkv; d.K = m.d_model; d.xb = s->h; d.epi = EPI_QKV; d.q = s->q;
             launch_decode_linear_mfma(d, sb, st);
         }
         {
             DecodeAttn a{};
-            a.q = s->q; a.o = s->o; a.o_dtype = DT_BF16; a.nb = B; a.hq = m.n_heads; a.kv_dtype = DT_BF16; a.kv = kvv;
+            a.q = s->q; a.o = s->o; a.o_dtype = DT_F16; a.nb = B; a.hq = m.n_heads; a.kv_dtype = DT_F16; a.kv = kvv;
             a.nsplit = pick_nsplit(s, sb); a.part_o = s->part_o; a.part_ml = s->part_ml;
             Bracket t(s, SHARD_K_DECODE_ATTN, st);
             launch_decode_attn(a, sb, st);
@@ -312,7 +313,7 @@ void run_decode_mfma(shard* s, const SeqBatch& sb, const float* x_in, float* x_o
         }
         {
             Bracket t(s, SHARD_K_DECODE_GATEUP, st);
-            launch_rmsnorm(x_out, l.g_ffn, m.rms_eps, s->h, DT_BF16, B, m.d_model, st);
+            launch_rmsnorm(x_out, l.g_ffn, m.rms_eps, s->h, DT_F16, B, m.d_model, st);
             d.W = l.wgu; d.N = 2 * m.ffn_dim; d.K = m.d_model; d.xb = s->h; d.epi = EPI_SWIGLU; d.out_b = s->f;
             launch_decode_linear_mfma(d, sb, st);
         }
@@ -355,7 +356,8 @@ void run_decode(shard* s, const SeqBatch& sb, const float* x_in, float* x_out, h
         }
         {
             DecodeAttn a{};
-            a.q = s->q; a.o = o; a.o_dtype = DT_F32; a.nb = B; a.hq = m.n_heads; a.kv_dtype = dt; a.kv = kvv;
+            a.q = s->q; a.o = o; a.o_dtype = DT_F32; a.nb = B; a.hq = m.n_heads;
+            a.kv_dtype = dt == DT_F32 ? DT_F32 : DT_F16; a.kv = kvv;
             a.nsplit = pick_nsplit(s, sb); a.part_o = s->part_o; a.part_ml = s->part_ml;
             Bracket t(s, SHARD_K_DECODE_ATTN, st);
             launch_decode_attn(a, sb, st);
