@@ -60,10 +60,15 @@ typedef struct {
     int32_t ffn_dim;      /* SwiGLU inner width F */
     float rms_eps;
     float rope_theta;
-    int32_t weight_dtype; /* dtype of the matrices.  SHARD_F32: KV cache and all arithmetic fp32.
-                             SHARD_BF16: fp32 accumulation and residual stream; the KV cache and the
-                             activations fed to the matrix cores are IEEE half (same 2 bytes per
-                             element as bf16, 8x finer rounding; bf16 weights convert to it exactly) */
+    int32_t weight_dtype; /* dtype of the matrices handed to shard_create.
+                             SHARD_F32: KV cache and all arithmetic fp32.
+                             SHARD_BF16: the matrices are converted ONCE, at create, to IEEE half
+                             (same 2 bytes per element; every bf16 value of magnitude 6.1e-5 ..
+                             65504 converts exactly, smaller ones round onto half's subnormal grid,
+                             absolute error <= 3e-8; a larger one makes shard_create fail with
+                             SHARD_E_INVAL).  The KV cache and the activations fed to the matrix
+                             cores are half as well (8x finer rounding than bf16); accumulation and
+                             the residual stream are fp32. */
     int32_t act_dtype;    /* dtype of x_in / x_out at the boundary; only SHARD_F32 is supported:
                              the paper runs full precision, and an fp32 hand-off keeps shard
                              composition exact.  The residual stream inside is always fp32. */

@@ -199,15 +199,15 @@ static void launch_dl_t(const DecodeLinear& a, const SeqBatch& sb, hipStream_t s
 
 void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
     if (a.wt == DT_F32) launch_dl_t<float>(a, sb, st);
-    else launch_dl_t<bf16_t>(a, sb, st);
+    else launch_dl_t<f16_t>(a, sb, st);
 }
 
 // ---------------------------------------------------------------------------------------
-// Linear layer for 9..16 activation rows with bf16 weights: at 16 FMAs per weight element
+// Linear layer for 9..16 activation rows with 16-bit weights: at 16 FMAs per weight element
 // the vector ALUs could no longer keep up with the HBM stream, so the products run on the
 // matrix cores: D[n][b] = sum_k W[n][k] x[b][k] with v_mfma_f32_16x16x32_bf16, the 16
 // activation rows filling the MFMA's second dimension exactly.
-// A workgroup owns 32 consecutive rows of W (two MFMA row tiles); its four waves split K
+// A workgroup owns 16 or 32 consecutive rows of W (one or two MFMA row tiles); its four waves split K
 // in interleaved 64-element blocks and meet in LDS (fixed order).  Lane (row = lane%16,
 // g = lane/16) supplies elements 32*j + 8*g + (0..7) of a block to MFMA j on both operands,
 // so every load instruction reads 64 contiguous bytes per row.  Activations arrive already
@@ -216,29 +216,29 @@ void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t
 typedef _Float16 f16x8_d __attribute__((ext_vector_type(8)));
 typedef float f32x4_d __attribute__((ext_vector_type(4)));
 
-template <int U>
+template <int TILES, int U>
 __global__ __launch_bounds__(256) void decode_linear_mfma_kernel(DecodeLinear a, SeqBatch sb) {
-    constexpr int ROWS = 32;
+    constexpr int ROWS = 16 * TILES;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, g = lane >> 4;
     const int row0 = blockIdx.x * ROWS;
-    const bf16_t* __restrict__ W = static_cast<const bf16_t*>(a.W);
+    const f16_t* __restrict__ W = static_cast<const f16_t*>(a.W);
     const f16_t* __restrict__ X = static_cast<const f16_t*>(a.xb);
     const int K = a.K, nblk = K / 64;  // K is a multiple of 64 on this path
 
-    const bf16_t* wp[2];
+    const f16_t* wp[TILES];
 #pragma unroll
-    for (int t = 0; t < 2; ++t) wp[t] = W + static_cast<size_t>(min(row0 + t * 16 + l16, a.N - 1)) * K + g * 8;
+    for (int t = 0; t < TILES; ++t) wp[t] = W + static_cast<size_t>(min(row0 + t * 16 + l16, a.N - 1)) * K + g * 8;
     const f16_t* xp = X + static_cast<size_t>(l16 < a.nb ? l16 : 0) * K + g * 8;
 
-    f32x4_d acc[2];
+    f32x4_d acc[TILES];
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < TILES; ++t)
 #pragma unroll
         for (int v = 0; v < 4; ++v) acc[t][v] = 0.f;
 
     for (int kb0 = wave; kb0 < nblk; kb0 += 4 * U) {
-        uint4 wv[U][2][2], xv[U][2];
+        uint4 wv[U][TILES][2], xv[U][2];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int kb = kb0 + 4 * u;
@@ -246,7 +246,7 @@ __global__ __launch_bounds__(256) void decode_linear_mfma_kernel(DecodeLinear a,
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
 #pragma unroll
-                for (int t = 0; t < 2; ++t) wv[u][t][j] = *reinterpret_cast<const uint4*>(wp[t] + kc * 64 + j * 32);
+                for (int t = 0; t < TILES; ++t) wv[u][t][j] = *reinterpret_cast<const uint4*>(wp[t] + kc * 64 + j * 32);
                 xv[u][j] = kb < nblk ? *reinterpret_cast<const uint4*>(xp + kc * 64 + j * 32) : make_uint4(0u, 0u, 0u, 0u);
             }
         }
@@ -255,22 +255,21 @@ __global__ __launch_bounds__(256) void decode_linear_mfma_kernel(DecodeLinear a,
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
-                for (int t = 0; t < 2; ++t)
-                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
-                        __builtin_bit_cast(f16x8_d, bf16x8_to_f16x8(wv[u][t][j])),
-                        __builtin_bit_cast(f16x8_d, xv[u][j]), acc[t], 0, 0, 0);
+                for (int t = 0; t < TILES; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_d, wv[u][t][j]),
+                                                                    __builtin_bit_cast(f16x8_d, xv[u][j]), acc[t], 0, 0, 0);
     }
 
     // D[n][b]: register v of a lane is row 4*g + v of its tile, activation row l16
     __shared__ float s_red[4][ROWS][16];
     __shared__ float s_val[ROWS][16];
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < TILES; ++t)
 #pragma unroll
         for (int v = 0; v < 4; ++v) s_red[wave][t * 16 + g * 4 + v][l16] = acc[t][v];
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < TILES; ++i) {
         const int id = tid + 256 * i, r = id >> 4, b = id & 15;
         s_val[r][b] = (s_red[0][r][b] + s_red[1][r][b]) + (s_red[2][r][b] + s_red[3][r][b]);
     }
@@ -278,7 +277,7 @@ __global__ __launch_bounds__(256) void decode_linear_mfma_kernel(DecodeLinear a,
 
     if (a.epi == EPI_RESID) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < TILES; ++i) {
             const int id = tid + 256 * i, r = id >> 4, b = id & 15, n = row0 + r;
             if (n < a.N && b < a.nb) {
                 const size_t at = static_cast<size_t>(b) * a.N + n;
@@ -290,7 +289,7 @@ __global__ __launch_bounds__(256) void decode_linear_mfma_kernel(DecodeLinear a,
     // pair epilogues: thread -> (row pair j, activation row b)
     const int j = tid >> 4, b = tid & 15;
     const int n0 = row0 + 2 * j;
-    if (n0 >= a.N || b >= a.nb) return;
+    if (2 * j >= ROWS || n0 >= a.N || b >= a.nb) return;
     const float v0 = s_val[2 * j][b], v1 = s_val[2 * j + 1][b];
     if (a.epi == EPI_SWIGLU) {
         const int F = a.N / 2;
@@ -325,8 +324,10 @@ __global__ __launch_bounds__(256) void decode_linear_mfma_kernel(DecodeLinear a,
 }
 
 void launch_decode_linear_mfma(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
-    const int grid = (a.N + 31) / 32;
-    hipLaunchKernelGGL(decode_linear_mfma_kernel<4>, dim3(grid), dim3(256), 0, st, a, sb);
+    // two row tiles per workgroup halve the activation reads; one tile when that would
+    // leave fewer than ~4 workgroups per compute unit
+    if (a.N >= 32 * 1024) hipLaunchKernelGGL((decode_linear_mfma_kernel<2, 4>), dim3((a.N + 31) / 32), dim3(256), 0, st, a, sb);
+    else hipLaunchKernelGGL((decode_linear_mfma_kernel<1, 4>), dim3((a.N + 15) / 16), dim3(256), 0, st, a, sb);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -504,6 +505,33 @@ void launch_decode_attn(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st)
 int decode_attn_tokens_per_trip(int kv_dtype, int dh) {
     const int vec = kv_dtype == DT_F32 ? 4 : 8;
     return 4 * 256 / (dh / vec);
+}
+
+// bf16 -> half, in place, 8 elements per thread
+__global__ __launch_bounds__(256) void bf16_to_f16_kernel(uint16_t* buf, size_t n8, uint32_t* overflow) {
+    const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= n8) return;
+    uint4* p = reinterpret_cast<uint4*>(buf) + i;
+    const uint4 w = *p;
+    const uint32_t in[4] = {w.x, w.y, w.z, w.w};
+    uint32_t out[4];
+    bool over = false;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float lo = __uint_as_float(in[j] << 16), hi = __uint_as_float(in[j] & 0xFFFF0000u);
+        over = over || fabsf(lo) > 65504.f || fabsf(hi) > 65504.f;
+        const f16_t hl = static_cast<f16_t>(lo), hh = static_cast<f16_t>(hi);
+        out[j] = static_cast<uint32_t>(__builtin_bit_cast(uint16_t, hl)) |
+                 (static_cast<uint32_t>(__builtin_bit_cast(uint16_t, hh)) << 16);
+    }
+    *p = make_uint4(out[0], out[1], out[2], out[3]);
+    if (over) *overflow = 1u;
+}
+
+void launch_bf16_to_f16(void* buf, size_t n, uint32_t* overflow, hipStream_t st) {
+    const size_t n8 = n / 8;  // matrices here have a multiple of 8 elements per row
+    hipLaunchKernelGGL(bf16_to_f16_kernel, dim3(static_cast<unsigned>((n8 + 255) / 256)), dim3(256), 0, st,
+                       static_cast<uint16_t*>(buf), n8, overflow);
 }
 
 __global__ void table_update_kernel(int32_t* table, TableUpdate u) {

@@ -40,26 +40,10 @@ template <> struct Elem<f16_t> {
     __device__ static __forceinline__ f16_t from_f32(float v) { return static_cast<f16_t>(v); }
 };
 
-// 16-bit format that goes with a weight type: activations fed to the matrix cores and the
-// KV cache.  bf16 weights pair with IEEE half: its 11-bit significand keeps the rounding
-// of activations 8x smaller than bf16 would, and every bf16 weight in half's normal range
-// converts to half exactly (8-bit significand).
+// Activation / KV-cache element type that goes with a weight element type.
 template <typename WT> struct ActOf;
 template <> struct ActOf<float> { typedef float type; };
-template <> struct ActOf<bf16_t> { typedef f16_t type; };
-
-// 8 bf16 (16 bytes) -> 8 half (16 bytes); exact for values in half's normal range
-__device__ __forceinline__ uint4 bf16x8_to_f16x8(const uint4& w) {
-    typedef __fp16 h2 __attribute__((ext_vector_type(2)));
-    const uint32_t in[4] = {w.x, w.y, w.z, w.w};
-    uint32_t out[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const h2 p = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(in[i] << 16), __uint_as_float(in[i] & 0xFFFF0000u));
-        out[i] = __builtin_bit_cast(uint32_t, p);
-    }
-    return make_uint4(out[0], out[1], out[2], out[3]);
-}
+template <> struct ActOf<f16_t> { typedef f16_t type; };
 
 // Load 16 bytes at p (16-byte aligned) and widen to fp32: 4 floats or 8 bf16.
 template <typename T> struct Vec16;

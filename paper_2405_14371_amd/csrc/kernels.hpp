@@ -8,7 +8,9 @@
 
 namespace shk {
 
-enum DType { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };  // bf16: weights only; f16: activations and KV cache
+// Element types inside the library.  bf16 only exists at the boundary: shard_create converts
+// bf16 matrices to IEEE half once (launch_bf16_to_f16).
+enum DType { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };
 
 // One layer's paged KV cache.  Element (page p, kv head h, slot s, e) of K or V lives at
 // ((p * hkv + h) * page + s) * dh + e; token u of sequence q is in page
@@ -49,7 +51,7 @@ struct DecodeLinear {
     void* out_b;           // EPI_SWIGLU output [nb, N/2] half
 };
 void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st);
-// same contract with xb/out_b; requires wt == DT_BF16, nb <= 16, K % 64 == 0, gain == null
+// same contract with xb/out_b; requires wt == DT_F16, nb <= 16, K % 64 == 0, gain == null
 void launch_decode_linear_mfma(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st);
 
 struct DecodeAttn {
@@ -101,6 +103,10 @@ struct PrefillAttn {
     KvView kv;
 };
 void launch_prefill_attn(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st);
+
+// In place: n bf16 values -> n IEEE half values (round to nearest; exact for every bf16 in
+// half's normal range).  *overflow is set when a finite value exceeds half's range.
+void launch_bf16_to_f16(void* buf, size_t n, uint32_t* overflow, hipStream_t st);
 
 // block_table[idx[i]] = val[i] for i < n (n <= 128), stream-ordered.
 struct TableUpdate {

@@ -98,16 +98,15 @@ __device__ __forceinline__ void gemm_epilogue(const PrefillGemm& a, const SeqBat
 }
 
 // ---------------------------------------------------------------------------------------
-// GEMM on the matrix cores, fp32 accumulation: v_mfma_f32_32x32x2_f32 for fp32 weights and
-// activations; for bf16 weights the activations are IEEE half, the weight tile is converted
-// to half (exactly) on its way into LDS, and the product runs on v_mfma_f32_32x32x16_f16.
+// GEMM on the matrix cores, fp32 accumulation: v_mfma_f32_32x32x2_f32 for fp32 operands,
+// v_mfma_f32_32x32x16_f16 for half operands.
 // Workgroup tile BN (features) x BM (rows), four waves in a 2x2 arrangement, each owning
 // (BN/2) x (BM/2) as 32x32 MFMA tiles.  K is walked in steps of 64 bytes per row (16 fp32
-// or 32 bf16) through two LDS stages: the global loads of step k+1 are in flight while
+// or 32 half) through two LDS stages: the global loads of step k+1 are in flight while
 // step k is multiplied.  LDS rows are k-contiguous with a pitch of 20 dwords, which makes
 // the 16-byte fragment reads conflict-free.  Within a 32-byte k group the lane with
 // half = lane/32 supplies the 16 bytes at offset 16*half - for fp32 that is a permutation
-// of k (the same on both operands, so the sum over k is unchanged), for bf16 it is the
+// of k (the same on both operands, so the sum over k is unchanged), for half it is the
 // instruction's native operand layout.
 // ---------------------------------------------------------------------------------------
 constexpr int GEMM_ROW_DW = 16;   // dwords of k per row per step
@@ -125,7 +124,7 @@ __device__ __forceinline__ void mfma_chunk<float>(const float4& w, const float4&
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.w, x.w, acc, 0, 0, 0);
 }
 template <>
-__device__ __forceinline__ void mfma_chunk<bf16_t>(const float4& w, const float4& x, f32x16& acc) {
+__device__ __forceinline__ void mfma_chunk<f16_t>(const float4& w, const float4& x, f32x16& acc) {
     acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, w), __builtin_bit_cast(f16x8_t, x),
                                                  acc, 0, 0, 0);
 }
@@ -169,8 +168,6 @@ __global__ __launch_bounds__(256) void gemm_kernel(PrefillGemm a, SeqBatch sb, i
             const bool ok = (n0 + row < a.N) && (k < a.K);
             gw[i] = ok ? *reinterpret_cast<const float4*>(W + static_cast<size_t>(n0 + row) * a.K + k)
                        : make_float4(0.f, 0.f, 0.f, 0.f);
-            if constexpr (sizeof(T) == 2)  // bf16 weights meet half activations: convert the tile once
-                gw[i] = __builtin_bit_cast(float4, bf16x8_to_f16x8(__builtin_bit_cast(uint4, gw[i])));
         }
 #pragma unroll
         for (int i = 0; i < LX; ++i) {
@@ -252,7 +249,7 @@ static void launch_gemm_t(const PrefillGemm& a, const SeqBatch& sb, hipStream_t 
 
 void launch_prefill_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
     if (a.dt == DT_F32) launch_gemm_t<float>(a, sb, st);
-    else launch_gemm_t<bf16_t>(a, sb, st);
+    else launch_gemm_t<f16_t>(a, sb, st);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -377,6 +374,129 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(PrefillAttn a, SeqBat
         }
 }
 
+// Same algorithm for a half cache on v_mfma_f32_32x32x16_f16: 16 keys or 16 head-dims per
+// instruction instead of 2.  K fragments are 16-byte loads (8 consecutive head dims of one
+// key); Q is converted to half (already scaled) once; P^T leaves the softmax in registers
+// 8m..8m+7 exactly as MFMA m of the PV product wants its B operand (keys 16m + 8b + 4*half
+// + i, b < 2, i < 4); V^T is gathered with 2-byte loads for the same keys.
+template <typename OT, int DH>
+__global__ __launch_bounds__(256) void prefill_attn_f16_kernel(PrefillAttn a, SeqBatch sb) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int qt = gridDim.x - 1 - blockIdx.x;  // longest rows first
+    const int h = blockIdx.y * 4 + wave;
+    const int b = blockIdx.z;
+    if (h >= a.hq) return;
+    const int hk = h / (a.hq / a.kv.hkv);
+    const int P = sb.pos[b];
+    const int32_t* bt = a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages;
+    const f16_t* __restrict__ kp = static_cast<const f16_t*>(a.kv.k);
+    const f16_t* __restrict__ vp = static_cast<const f16_t*>(a.kv.v);
+    const int ctx = P + a.T;
+    const int page = a.kv.page, hkv = a.kv.hkv;
+
+    const int t_q = qt * 32 + l32;
+    const int t_ld = min(t_q, a.T - 1);
+    const size_t qrow = (static_cast<size_t>(b) * a.T + t_ld) * a.hq * DH + h * DH;
+    const float scale = 1.0f / sqrtf(static_cast<float>(DH));
+    f16x8_t qf[DH / 16];
+#pragma unroll
+    for (int j = 0; j < DH / 16; ++j) {
+        const float4 lo = *reinterpret_cast<const float4*>(a.q + qrow + j * 16 + half * 8);
+        const float4 hi = *reinterpret_cast<const float4*>(a.q + qrow + j * 16 + half * 8 + 4);
+        qf[j][0] = static_cast<f16_t>(lo.x * scale); qf[j][1] = static_cast<f16_t>(lo.y * scale);
+        qf[j][2] = static_cast<f16_t>(lo.z * scale); qf[j][3] = static_cast<f16_t>(lo.w * scale);
+        qf[j][4] = static_cast<f16_t>(hi.x * scale); qf[j][5] = static_cast<f16_t>(hi.y * scale);
+        qf[j][6] = static_cast<f16_t>(hi.z * scale); qf[j][7] = static_cast<f16_t>(hi.w * scale);
+    }
+    f32x16 o[DH / 32];
+#pragma unroll
+    for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[j][v] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+    const int pos_q = P + t_q;
+    const int last_key = P + min(qt * 32 + 31, a.T - 1);
+
+    for (int k0 = 0; k0 <= last_key; k0 += 32) {
+        const int u = min(k0 + l32, ctx - 1);
+        const size_t kat = ((static_cast<size_t>(bt[u / page]) * hkv + hk) * page + u % page) * DH + half * 8;
+        f32x16 s;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[v] = 0.f;
+#pragma unroll
+        for (int j = 0; j < DH / 16; ++j) {
+            const f16x8_t kf = *reinterpret_cast<const f16x8_t*>(kp + kat + j * 16);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[j], s, 0, 0, 0);
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int key = k0 + (v >> 2) * 8 + half * 4 + (v & 3);
+            if (key > pos_q) s[v] = -INFINITY;
+            mx = fmaxf(mx, s[v]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float corr = __expf(m_run - m_use);
+        float rs = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            s[v] = __expf(s[v] - m_use);
+            rs += s[v];
+        }
+        rs += __shfl_xor(rs, 32, 64);
+        l_run = l_run * corr + rs;
+        m_run = m_new;
+#pragma unroll
+        for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[j][v] *= corr;
+#pragma unroll
+        for (int mm = 0; mm < 2; ++mm) {
+            f16x8_t pf;
+            size_t vat[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                pf[i] = static_cast<f16_t>(s[mm * 8 + i]);
+                // register 8*mm + i of this lane is key 16*mm + 8*(i/4) + 4*half + i%4
+                const int key = min(k0 + mm * 16 + (i >> 2) * 8 + half * 4 + (i & 3), ctx - 1);
+                vat[i] = ((static_cast<size_t>(bt[key / page]) * hkv + hk) * page + key % page) * DH + l32;
+            }
+#pragma unroll
+            for (int j = 0; j < DH / 32; ++j) {
+                f16x8_t vf;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) vf[i] = vp[vat[i] + j * 32];
+                o[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf, o[j], 0, 0, 0);
+            }
+        }
+    }
+
+    if (t_q >= a.T) return;
+    const float inv = 1.0f / l_run;
+    OT* op = static_cast<OT*>(a.o) + (static_cast<size_t>(b) * a.T + t_q) * a.hq * DH + h * DH;
+#pragma unroll
+    for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+            const int d = j * 32 + vq * 8 + half * 4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) op[d + i] = Elem<OT>::from_f32(o[j][vq * 4 + i] * inv);
+        }
+}
+
+template <typename OT>
+static void launch_pa_f16(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st) {
+    const dim3 grid((a.T + 31) / 32, (a.hq + 3) / 4, a.B), block(256);
+    switch (a.kv.dh) {
+        case 32: hipLaunchKernelGGL((prefill_attn_f16_kernel<OT, 32>), grid, block, 0, st, a, sb); break;
+        case 64: hipLaunchKernelGGL((prefill_attn_f16_kernel<OT, 64>), grid, block, 0, st, a, sb); break;
+        default: hipLaunchKernelGGL((prefill_attn_f16_kernel<OT, 128>), grid, block, 0, st, a, sb); break;
+    }
+}
+
 template <typename KT, typename OT>
 static void launch_pa(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st) {
     const dim3 grid((a.T + 31) / 32, (a.hq + 3) / 4, a.B), block(256);
@@ -392,8 +512,8 @@ void launch_prefill_attn(const PrefillAttn& a, const SeqBatch& sb, hipStream_t s
         if (a.out_dtype == DT_F32) launch_pa<float, float>(a, sb, st);
         else launch_pa<float, f16_t>(a, sb, st);
     } else {
-        if (a.out_dtype == DT_F32) launch_pa<f16_t, float>(a, sb, st);
-        else launch_pa<f16_t, f16_t>(a, sb, st);
+        if (a.out_dtype == DT_F32) launch_pa_f16<float>(a, sb, st);
+        else launch_pa_f16<f16_t>(a, sb, st);
     }
 }
 

@@ -220,7 +220,7 @@ void mark_layer(shard* s, int i, hipStream_t st) {
 void run_prefill(shard* s, const SeqBatch& sb, int T, const float* x_in, float* x_out, hipStream_t st) {
     const shard_model_cfg& m = s->m;
     const int M = sb.n * T;
-    const int dt = m.weight_dtype == SHARD_F32 ? DT_F32 : DT_BF16;   // weights
+    const int dt = m.weight_dtype == SHARD_F32 ? DT_F32 : DT_F16;    // weights as stored on the device
     const int adt = m.weight_dtype == SHARD_F32 ? DT_F32 : DT_F16;   // activations and KV cache
     mark_layer(s, 0, st);
     for (int li = 0; li < s->L; ++li) {
@@ -273,7 +273,7 @@ int pick_nsplit(const shard* s, const SeqBatch& sb) {
     int ctx = 1;
     for (int b = 0; b < sb.n; ++b) ctx = ctx > sb.pos[b] + 1 ? ctx : sb.pos[b] + 1;
     const int units = sb.n * s->m.n_heads;
-    const int trip = decode_attn_tokens_per_trip(s->m.weight_dtype == SHARD_F32 ? DT_F32 : DT_BF16, s->m.head_dim);
+    const int trip = decode_attn_tokens_per_trip(s->m.weight_dtype == SHARD_F32 ? DT_F32 : DT_F16, s->m.head_dim);
     int n = (ctx + trip - 1) / trip;
     const int cap = (2048 + units - 1) / units;
     if (n > cap) n = cap;
@@ -292,7 +292,7 @@ void run_decode_mfma(shard* s, const SeqBatch& sb, const float* x_in, float* x_o
         const float* x = li == 0 ? x_in : x_out;
         const KvView kvv = kv_view(s, li);
         DecodeLinear d{};
-        d.wt = DT_BF16; d.nb = B; d.hq = m.n_heads; d.kv = kvv; d.rope = s->rope;
+        d.wt = DT_F16; d.nb = B; d.hq = m.n_heads; d.kv = kvv; d.rope = s->rope;
         {
             Bracket t(s, SHARD_K_DECODE_QKV, st);
             launch_rmsnorm(x, l.g_attn, m.rms_eps, s->h, DT_F16, B, m.d_model, st);
@@ -328,9 +328,9 @@ void run_decode_mfma(shard* s, const SeqBatch& sb, const float* x_in, float* x_o
 
 void run_decode(shard* s, const SeqBatch& sb, const float* x_in, float* x_out, hipStream_t st) {
     const shard_model_cfg& m = s->m;
-    const int dt = m.weight_dtype == SHARD_F32 ? DT_F32 : DT_BF16;
+    const int dt = m.weight_dtype == SHARD_F32 ? DT_F32 : DT_F16;
     const int B = sb.n;
-    if (dt == DT_BF16 && B > 8 && B <= 16 && m.d_model % 64 == 0 && m.ffn_dim % 64 == 0 && s->nq % 64 == 0) {
+    if (dt == DT_F16 && B > 8 && B <= 16 && m.d_model % 64 == 0 && m.ffn_dim % 64 == 0 && s->nq % 64 == 0) {
         run_decode_mfma(s, sb, x_in, x_out, st);
         return;
     }
@@ -357,7 +357,7 @@ void run_decode(shard* s, const SeqBatch& sb, const float* x_in, float* x_out, h
         {
             DecodeAttn a{};
             a.q = s->q; a.o = o; a.o_dtype = DT_F32; a.nb = B; a.hq = m.n_heads;
-            a.kv_dtype = dt == DT_F32 ? DT_F32 : DT_F16; a.kv = kvv;
+            a.kv_dtype = dt; a.kv = kvv;
             a.nsplit = pick_nsplit(s, sb); a.part_o = s->part_o; a.part_ml = s->part_ml;
             Bracket t(s, SHARD_K_DECODE_ATTN, st);
             launch_decode_attn(a, sb, st);
@@ -447,6 +447,7 @@ int shard_create(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg
     } while (0)
 
     const size_t page_elems = static_cast<size_t>(model->n_kv_heads) * kv->page_size * dh;
+    uint32_t* cvt_flag = nullptr;
     for (int i = 0; i < L; ++i) {
         LayerDev& l = s->layers[i];
         CREATE_TRY(hipMalloc(&l.wqkv, static_cast<size_t>(s->nqkv) * d * es));
@@ -467,6 +468,17 @@ int shard_create(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg
         CREATE_TRY(hipMemcpy2D(l.wgu, 2 * rowb, w[i].w_gate, rowb, rowb, F, kind));
         CREATE_TRY(hipMemcpy2D(static_cast<char*>(l.wgu) + rowb, 2 * rowb, w[i].w_up, rowb, rowb, F, kind));
         CREATE_TRY(hipMemcpy(l.wd, w[i].w_down, static_cast<size_t>(d) * F * es, kind));
+        if (model->weight_dtype == SHARD_BF16) {
+            // bf16 exists only at the boundary: the matrices live on the device as IEEE half
+            if (!cvt_flag) {
+                CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&cvt_flag), sizeof(uint32_t)));
+                CREATE_TRY(hipMemset(cvt_flag, 0, sizeof(uint32_t)));
+            }
+            launch_bf16_to_f16(l.wqkv, static_cast<size_t>(s->nqkv) * d, cvt_flag, nullptr);
+            launch_bf16_to_f16(l.wo, static_cast<size_t>(d) * s->nq, cvt_flag, nullptr);
+            launch_bf16_to_f16(l.wgu, static_cast<size_t>(2) * F * d, cvt_flag, nullptr);
+            launch_bf16_to_f16(l.wd, static_cast<size_t>(d) * F, cvt_flag, nullptr);
+        }
         CREATE_TRY(hipMemcpy(l.g_attn, w[i].g_attn, d * sizeof(float), kind));
         CREATE_TRY(hipMemcpy(l.g_ffn, w[i].g_ffn, d * sizeof(float), kind));
         // a cache that was never written must still hold finite numbers (masked lanes read it)
@@ -508,6 +520,16 @@ int shard_create(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg
     for (auto& e : s->layer_ev) e = nullptr;
     for (auto& e : s->layer_ev) CREATE_TRY(hipEventCreate(&e));
     CREATE_TRY(hipDeviceSynchronize());
+    if (cvt_flag) {
+        uint32_t over = 0;
+        const hipError_t e1 = hipMemcpy(&over, cvt_flag, sizeof over, hipMemcpyDeviceToHost);
+        (void)hipFree(cvt_flag);
+        if (e1 != hipSuccess || over) {
+            free_all(s);
+            return e1 != hipSuccess ? fail(SHARD_E_HIP, "reading the conversion flag: %s", hipGetErrorString(e1))
+                                    : fail(SHARD_E_INVAL, "a bf16 weight exceeds the range of IEEE half (65504)");
+        }
+    }
 #undef CREATE_TRY
     *out = s;
     return SHARD_OK;
