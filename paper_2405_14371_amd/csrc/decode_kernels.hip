@@ -216,9 +216,10 @@ void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t
 typedef _Float16 f16x8_d __attribute__((ext_vector_type(8)));
 typedef float f32x4_d __attribute__((ext_vector_type(4)));
 
-template <int TILES, int U>
-__global__ __launch_bounds__(256) void decode_linear_mfma_kernel(DecodeLinear a, SeqBatch sb) {
+template <int TILES, int U, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLinear a, SeqBatch sb) {
     constexpr int ROWS = 16 * TILES;
+    constexpr int THREADS = 64 * WAVES;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, g = lane >> 4;
     const int row0 = blockIdx.x * ROWS;
@@ -237,11 +238,11 @@ __global__ __launch_bounds__(256) void decode_linear_mfma_kernel(DecodeLinear a,
 #pragma unroll
         for (int v = 0; v < 4; ++v) acc[t][v] = 0.f;
 
-    for (int kb0 = wave; kb0 < nblk; kb0 += 4 * U) {
+    for (int kb0 = wave; kb0 < nblk; kb0 += WAVES * U) {
         uint4 wv[U][TILES][2], xv[U][2];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int kb = kb0 + 4 * u;
+            const int kb = kb0 + WAVES * u;
             const int kc = kb < nblk ? kb : kb0;  // past the end: re-read a valid block, zero its activations
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
@@ -261,24 +262,25 @@ __global__ __launch_bounds__(256) void decode_linear_mfma_kernel(DecodeLinear a,
     }
 
     // D[n][b]: register v of a lane is row 4*g + v of its tile, activation row l16
-    __shared__ float s_red[4][ROWS][16];
+    __shared__ float s_red[WAVES][ROWS][16];
     __shared__ float s_val[ROWS][16];
 #pragma unroll
     for (int t = 0; t < TILES; ++t)
 #pragma unroll
         for (int v = 0; v < 4; ++v) s_red[wave][t * 16 + g * 4 + v][l16] = acc[t][v];
     __syncthreads();
+    for (int id = tid; id < ROWS * 16; id += THREADS) {
+        const int r = id >> 4, b = id & 15;
+        float v = 0.f;
 #pragma unroll
-    for (int i = 0; i < TILES; ++i) {
-        const int id = tid + 256 * i, r = id >> 4, b = id & 15;
-        s_val[r][b] = (s_red[0][r][b] + s_red[1][r][b]) + (s_red[2][r][b] + s_red[3][r][b]);
+        for (int w = 0; w < WAVES; ++w) v += s_red[w][r][b];
+        s_val[r][b] = v;
     }
     __syncthreads();
 
     if (a.epi == EPI_RESID) {
-#pragma unroll
-        for (int i = 0; i < TILES; ++i) {
-            const int id = tid + 256 * i, r = id >> 4, b = id & 15, n = row0 + r;
+        for (int id = tid; id < ROWS * 16; id += THREADS) {
+            const int r = id >> 4, b = id & 15, n = row0 + r;
             if (n < a.N && b < a.nb) {
                 const size_t at = static_cast<size_t>(b) * a.N + n;
                 a.out[at] = a.resid[at] + s_val[r][b];
@@ -287,9 +289,10 @@ __global__ __launch_bounds__(256) void decode_linear_mfma_kernel(DecodeLinear a,
         return;
     }
     // pair epilogues: thread -> (row pair j, activation row b)
+    if (tid >= ROWS * 8) return;   // ROWS/2 row pairs x 16 activation rows (needs THREADS >= ROWS*8)
     const int j = tid >> 4, b = tid & 15;
     const int n0 = row0 + 2 * j;
-    if (2 * j >= ROWS || n0 >= a.N || b >= a.nb) return;
+    if (n0 >= a.N || b >= a.nb) return;
     const float v0 = s_val[2 * j][b], v1 = s_val[2 * j + 1][b];
     if (a.epi == EPI_SWIGLU) {
         const int F = a.N / 2;
@@ -324,10 +327,12 @@ __global__ __launch_bounds__(256) void decode_linear_mfma_kernel(DecodeLinear a,
 }
 
 void launch_decode_linear_mfma(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
-    // two row tiles per workgroup halve the activation reads; one tile when that would
-    // leave fewer than ~4 workgroups per compute unit
-    if (a.N >= 32 * 1024) hipLaunchKernelGGL((decode_linear_mfma_kernel<2, 4>), dim3((a.N + 31) / 32), dim3(256), 0, st, a, sb);
-    else hipLaunchKernelGGL((decode_linear_mfma_kernel<1, 4>), dim3((a.N + 15) / 16), dim3(256), 0, st, a, sb);
+    // (row tiles per workgroup, waves splitting K) from a sweep on the 70B shapes: more row
+    // tiles re-use each activation fragment, more waves keep more loads in flight
+    if (a.N >= 10240)
+        hipLaunchKernelGGL((decode_linear_mfma_kernel<4, 2, 16>), dim3((a.N + 63) / 64), dim3(1024), 0, st, a, sb);
+    else
+        hipLaunchKernelGGL((decode_linear_mfma_kernel<2, 2, 8>), dim3((a.N + 31) / 32), dim3(512), 0, st, a, sb);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -109,8 +109,8 @@ __device__ __forceinline__ void gemm_epilogue(const PrefillGemm& a, const SeqBat
 // of k (the same on both operands, so the sum over k is unchanged), for half it is the
 // instruction's native operand layout.
 // ---------------------------------------------------------------------------------------
-constexpr int GEMM_ROW_DW = 16;   // dwords of k per row per step
-constexpr int GEMM_PITCH = 20;    // LDS row pitch in dwords
+// dwords of k per row per step (ROWDW) and LDS row pitch in dwords (PITCH) are template
+// parameters: (16, 20) and (32, 36) both give conflict-free 16-byte fragment reads.
 
 typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 
@@ -129,14 +129,16 @@ __device__ __forceinline__ void mfma_chunk<f16_t>(const float4& w, const float4&
                                                  acc, 0, 0, 0);
 }
 
-template <typename T, int BN, int BM>
+template <typename T, int BN, int BM, int ROWDW, int PITCH>
 __global__ __launch_bounds__(256) void gemm_kernel(PrefillGemm a, SeqBatch sb, int tiles_m, int tiles_total) {
     constexpr int VEC = Elem<T>::VEC;          // elements per 16 bytes
-    constexpr int BK = GEMM_ROW_DW / 4 * VEC;  // elements of k per step
+    constexpr int CH = ROWDW / 4;              // 16-byte chunks per row per step
+    constexpr int BK = CH * VEC;               // elements of k per step
     constexpr int TN = BN / 64, TM = BM / 64;  // MFMA tiles per wave
-    constexpr int LW = BN * 4 / 256, LX = BM * 4 / 256;  // 16-byte loads per thread per stage
-    __shared__ __attribute__((aligned(16))) float sW[2][BN * GEMM_PITCH];
-    __shared__ __attribute__((aligned(16))) float sX[2][BM * GEMM_PITCH];
+    constexpr int LW = BN * CH / 256, LX = BM * CH / 256;  // 16-byte loads per thread per stage
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    float* const sW0 = smem;                               // [2][BN * PITCH]
+    float* const sX0 = smem + 2 * BN * PITCH;              // [2][BM * PITCH]
 
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
     // tiles so that the workgroups sharing a W tile also share an L2.
@@ -164,14 +166,14 @@ __global__ __launch_bounds__(256) void gemm_kernel(PrefillGemm a, SeqBatch sb, i
     auto gload = [&](int k0) {
 #pragma unroll
         for (int i = 0; i < LW; ++i) {
-            const int idx = tid + 256 * i, row = idx >> 2, k = k0 + (idx & 3) * VEC;
+            const int idx = tid + 256 * i, row = idx / CH, k = k0 + (idx % CH) * VEC;
             const bool ok = (n0 + row < a.N) && (k < a.K);
             gw[i] = ok ? *reinterpret_cast<const float4*>(W + static_cast<size_t>(n0 + row) * a.K + k)
                        : make_float4(0.f, 0.f, 0.f, 0.f);
         }
 #pragma unroll
         for (int i = 0; i < LX; ++i) {
-            const int idx = tid + 256 * i, row = idx >> 2, k = k0 + (idx & 3) * VEC;
+            const int idx = tid + 256 * i, row = idx / CH, k = k0 + (idx % CH) * VEC;
             const bool ok = (m0 + row < a.M) && (k < a.K);
             gx[i] = ok ? *reinterpret_cast<const float4*>(X + static_cast<size_t>(m0 + row) * a.K + k)
                        : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -181,12 +183,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(PrefillGemm a, SeqBatch sb, i
 #pragma unroll
         for (int i = 0; i < LW; ++i) {
             const int idx = tid + 256 * i;
-            *reinterpret_cast<float4*>(&sW[stage][(idx >> 2) * GEMM_PITCH + (idx & 3) * 4]) = gw[i];
+            *reinterpret_cast<float4*>(&sW0[stage * BN * PITCH + (idx / CH) * PITCH + (idx % CH) * 4]) = gw[i];
         }
 #pragma unroll
         for (int i = 0; i < LX; ++i) {
             const int idx = tid + 256 * i;
-            *reinterpret_cast<float4*>(&sX[stage][(idx >> 2) * GEMM_PITCH + (idx & 3) * 4]) = gx[i];
+            *reinterpret_cast<float4*>(&sX0[stage * BM * PITCH + (idx / CH) * PITCH + (idx % CH) * 4]) = gx[i];
         }
     };
 
@@ -198,16 +200,16 @@ __global__ __launch_bounds__(256) void gemm_kernel(PrefillGemm a, SeqBatch sb, i
         const int stage = ks & 1;
         if (ks + 1 < ksteps) gload((ks + 1) * BK);
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
+        for (int kk = 0; kk < ROWDW / 8; ++kk) {
             float4 fw[TN], fx[TM];
 #pragma unroll
             for (int i = 0; i < TN; ++i)
                 fw[i] = *reinterpret_cast<const float4*>(
-                    &sW[stage][(wn * (BN / 2) + i * 32 + l32) * GEMM_PITCH + kk * 8 + half * 4]);
+                    &sW0[stage * BN * PITCH + (wn * (BN / 2) + i * 32 + l32) * PITCH + kk * 8 + half * 4]);
 #pragma unroll
             for (int j = 0; j < TM; ++j)
                 fx[j] = *reinterpret_cast<const float4*>(
-                    &sX[stage][(wm * (BM / 2) + j * 32 + l32) * GEMM_PITCH + kk * 8 + half * 4]);
+                    &sX0[stage * BM * PITCH + (wm * (BM / 2) + j * 32 + l32) * PITCH + kk * 8 + half * 4]);
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
@@ -231,25 +233,41 @@ __global__ __launch_bounds__(256) void gemm_kernel(PrefillGemm a, SeqBatch sb, i
             }
 }
 
-template <typename T, int BN, int BM>
+template <typename T, int BN, int BM, int ROWDW, int PITCH>
 static void launch_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
     const int total = tiles_m * tiles_n;
     const int grid = ((total + 7) / 8) * 8;
-    hipLaunchKernelGGL((gemm_kernel<T, BN, BM>), dim3(grid), dim3(256), 0, st, a, sb, tiles_m, total);
+    constexpr size_t lds = 2u * (BN + BM) * PITCH * sizeof(float);
+    static bool prepared = false;  // more than 64 KB of LDS per workgroup is an opt-in
+    if (!prepared) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<T, BN, BM, ROWDW, PITCH>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        prepared = true;
+    }
+    hipLaunchKernelGGL((gemm_kernel<T, BN, BM, ROWDW, PITCH>), dim3(grid), dim3(256), lds, st, a, sb, tiles_m, total);
 }
 
-template <typename T>
-static void launch_gemm_t(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
-    // the larger tile only when it still gives every compute unit two workgroups
+// Tile choice (measured on MI355X at M = 512 / 1024 on the Llama2 shapes): fp32 is MFMA-issue
+// bound, so the only concern is filling 256 compute units; for half operands wide matrices
+// run best with 64-byte k steps and three or four workgroups per compute unit, while the
+// narrow ones (N = d_model) have few tiles and gain from 128-byte k steps (half the barriers).
+static void launch_gemm_f32(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
     const long t128 = static_cast<long>((a.M + 127) / 128) * ((a.N + 127) / 128);
-    if (t128 >= 512) launch_gemm<T, 128, 128>(a, sb, st);
-    else launch_gemm<T, 128, 64>(a, sb, st);
+    if (t128 >= 512) launch_gemm<float, 128, 128, 16, 20>(a, sb, st);
+    else launch_gemm<float, 128, 64, 16, 20>(a, sb, st);
+}
+
+static void launch_gemm_f16(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
+    const long t128 = static_cast<long>((a.M + 127) / 128) * ((a.N + 127) / 128);
+    if (t128 >= 700) launch_gemm<f16_t, 128, 128, 16, 20>(a, sb, st);
+    else if (t128 >= 256) launch_gemm<f16_t, 128, 128, 32, 36>(a, sb, st);
+    else launch_gemm<f16_t, 128, 64, 32, 36>(a, sb, st);
 }
 
 void launch_prefill_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
-    if (a.dt == DT_F32) launch_gemm_t<float>(a, sb, st);
-    else launch_gemm_t<f16_t>(a, sb, st);
+    if (a.dt == DT_F32) launch_gemm_f32(a, sb, st);
+    else launch_gemm_f16(a, sb, st);
 }
 
 // ---------------------------------------------------------------------------------------
