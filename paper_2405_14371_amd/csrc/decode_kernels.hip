@@ -52,7 +52,7 @@ __global__ __launch_bounds__(256) void decode_linear_kernel(DecodeLinear a, SeqB
             ok[u] = c < nchunk;
             cc[u] = ok[u] ? c : c0;
 #pragma unroll
-            for (int r = 0; r < R; ++r) w[u][r].load(rowp[r] + static_cast<size_t>(cc[u]) * VEC);
+            for (int r = 0; r < R; ++r) w[u][r].load_stream(rowp[r] + static_cast<size_t>(cc[u]) * VEC);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
