@@ -18,10 +18,16 @@ KERNEL_CLASSES = ("decode_qkv", "decode_attn", "decode_o", "decode_gateup", "dec
                   "prefill_qkv", "prefill_attn", "prefill_o", "prefill_gateup", "prefill_down")
 K_COUNT = len(KERNEL_CLASSES)
 
+class PlanProblem(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_devices", C.c_int32), ("t_comp", C.POINTER(C.c_double)),
+                ("act_bytes", C.POINTER(C.c_double)), ("req_bytes", C.POINTER(C.c_double)),
+                ("mem_bytes", C.POINTER(C.c_double)), ("bandwidth", C.POINTER(C.c_double))]
+
+
 EXPORTS = (
     "shard_create", "shard_destroy", "shard_seq_alloc", "shard_seq_free", "shard_seq_len",
     "shard_prefill", "shard_decode", "shard_profile", "shard_timing_enable", "shard_timing_read",
-    "shard_last_error",
+    "shard_last_error", "shard_plan_latency", "shard_plan_throughput",
 )
 
 
@@ -80,6 +86,8 @@ def load():
     lib.shard_profile.argtypes = [vp, i32, i32, i32, i32, C.POINTER(LayerProfile)]
     lib.shard_timing_enable.argtypes = [vp, i32]
     lib.shard_timing_read.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+    lib.shard_plan_latency.argtypes = [C.POINTER(PlanProblem), C.POINTER(i32), C.POINTER(C.c_double)]
+    lib.shard_plan_throughput.argtypes = [C.POINTER(PlanProblem), i32, C.POINTER(i32), C.POINTER(C.c_double)]
     lib.shard_last_error.argtypes = []
     lib.shard_last_error.restype = C.c_char_p
     for name in EXPORTS:
@@ -207,3 +215,33 @@ def pack_layers(layers: list, weight_dtype: int) -> list:
                 d[k] = bf16_bits(v)
         out.append(d)
     return out
+
+
+def _plan_problem(prob: dict):
+    dbl = lambda a: np.ascontiguousarray(a, dtype=np.float64)
+    arrs = [dbl(prob[k]) for k in ("t_comp", "act_bytes", "req_bytes", "mem_bytes", "bandwidth")]
+    n, m = arrs[0].shape
+    ptr = lambda a: a.ctypes.data_as(C.POINTER(C.c_double))
+    return PlanProblem(n, m, *[ptr(a) for a in arrs]), arrs, n
+
+
+def plan_latency(prob: dict):
+    """shard_plan_latency: returns (total time of one token, device of each layer)."""
+    pp, keep, n = _plan_problem(prob)
+    dev = (C.c_int32 * n)()
+    t = C.c_double()
+    rc = load().shard_plan_latency(C.byref(pp), dev, C.byref(t))
+    if rc:
+        raise ShardError(rc, "no feasible placement" if rc == -2 else "bad planner arguments")
+    return t.value, list(dev)
+
+
+def plan_throughput(prob: dict, with_return_hop: bool = False):
+    """shard_plan_throughput: returns (slowest stage time, device of each layer)."""
+    pp, keep, n = _plan_problem(prob)
+    dev = (C.c_int32 * n)()
+    t = C.c_double()
+    rc = load().shard_plan_throughput(C.byref(pp), 1 if with_return_hop else 0, dev, C.byref(t))
+    if rc:
+        raise ShardError(rc, "no feasible placement" if rc == -2 else "bad planner arguments")
+    return t.value, list(dev)
