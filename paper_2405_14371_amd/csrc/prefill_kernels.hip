@@ -255,7 +255,7 @@ static void launch_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st
 static void launch_gemm_f32(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
     const long t128 = static_cast<long>((a.M + 127) / 128) * ((a.N + 127) / 128);
     if (t128 >= 512) launch_gemm<float, 128, 128, 16, 20>(a, sb, st);
-    else launch_gemm<float, 128, 64, 16, 20>(a, sb, st);
+    else launch_gemm<float, 128, 64, 32, 36>(a, sb, st);  // few tiles: longer k steps, half the barriers
 }
 
 static void launch_gemm_f16(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
