@@ -101,16 +101,21 @@ __device__ __forceinline__ void gemm_epilogue(const PrefillGemm& a, const SeqBat
 // GEMM on the matrix cores, fp32 accumulation: v_mfma_f32_32x32x2_f32 for fp32 operands,
 // v_mfma_f32_32x32x16_f16 for half operands.
 // Workgroup tile BN (features) x BM (rows), four waves in a 2x2 arrangement, each owning
-// (BN/2) x (BM/2) as 32x32 MFMA tiles.  K is walked in steps of 64 bytes per row (16 fp32
-// or 32 half) through two LDS stages: the global loads of step k+1 are in flight while
-// step k is multiplied.  LDS rows are k-contiguous with a pitch of 20 dwords, which makes
-// the 16-byte fragment reads conflict-free.  Within a 32-byte k group the lane with
+// (BN/2) x (BM/2) as 32x32 MFMA tiles.  K is walked in steps of ROWDW dwords per row (64 or
+// 128 bytes) through two LDS stages: the global loads of step k+1 are in flight while step k
+// is multiplied.  LDS rows are k-contiguous.  Within a 32-byte k group the lane with
 // half = lane/32 supplies the 16 bytes at offset 16*half - for fp32 that is a permutation
 // of k (the same on both operands, so the sum over k is unchanged), for half it is the
 // instruction's native operand layout.
+//
+// LDS layout: PITCH is the row pitch in dwords.  PITCH == ROWDW selects the unpadded,
+// XOR-swizzled layout: 16-byte chunk c of row r is stored at chunk c ^ g(r), g(r) = (r/4)%4
+// for 4-chunk rows and (r/2)%8 for 8-chunk rows.  Measured on MI355X (SQ_LDS_BANK_CONFLICT):
+// LDS serves 16-byte reads from 16 lanes per clock over 64 banks and 16-byte writes from 8
+// lanes per clock over 32 banks; the swizzle is conflict-free for both, while a padded pitch
+// (ROWDW + 4) is conflict-free for the reads only (its stores, two rows per 8 lanes, collide:
+// a third of the LDS cycles at ROWDW = 16).
 // ---------------------------------------------------------------------------------------
-// dwords of k per row per step (ROWDW) and LDS row pitch in dwords (PITCH) are template
-// parameters: (16, 20) and (32, 36) both give conflict-free 16-byte fragment reads.
 
 typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 
@@ -150,6 +155,11 @@ __global__ __launch_bounds__(256) void gemm_kernel(PrefillGemm a, SeqBatch sb, i
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wn = wave >> 1, wm = wave & 1;
     const int l32 = lane & 31, half = lane >> 5;
+    // dword offset of 16-byte chunk c of tile row r
+    auto lds_at = [](int r, int c) {
+        if constexpr (PITCH == ROWDW) return r * PITCH + ((c ^ (CH == 4 ? (r >> 2) & 3 : (r >> 1) & 7)) << 2);
+        else return r * PITCH + (c << 2);
+    };
     typedef typename ActOf<T>::type AT;  // activation type (same size as T)
     const T* __restrict__ W = static_cast<const T*>(a.W);
     const AT* __restrict__ X = static_cast<const AT*>(a.A);
@@ -183,12 +193,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(PrefillGemm a, SeqBatch sb, i
 #pragma unroll
         for (int i = 0; i < LW; ++i) {
             const int idx = tid + 256 * i;
-            *reinterpret_cast<float4*>(&sW0[stage * BN * PITCH + (idx / CH) * PITCH + (idx % CH) * 4]) = gw[i];
+            *reinterpret_cast<float4*>(&sW0[stage * BN * PITCH + lds_at(idx / CH, idx % CH)]) = gw[i];
         }
 #pragma unroll
         for (int i = 0; i < LX; ++i) {
             const int idx = tid + 256 * i;
-            *reinterpret_cast<float4*>(&sX0[stage * BM * PITCH + (idx / CH) * PITCH + (idx % CH) * 4]) = gx[i];
+            *reinterpret_cast<float4*>(&sX0[stage * BM * PITCH + lds_at(idx / CH, idx % CH)]) = gx[i];
         }
     };
 
@@ -205,11 +215,11 @@ __global__ __launch_bounds__(256) void gemm_kernel(PrefillGemm a, SeqBatch sb, i
 #pragma unroll
             for (int i = 0; i < TN; ++i)
                 fw[i] = *reinterpret_cast<const float4*>(
-                    &sW0[stage * BN * PITCH + (wn * (BN / 2) + i * 32 + l32) * PITCH + kk * 8 + half * 4]);
+                    &sW0[stage * BN * PITCH + lds_at(wn * (BN / 2) + i * 32 + l32, kk * 2 + half)]);
 #pragma unroll
             for (int j = 0; j < TM; ++j)
                 fx[j] = *reinterpret_cast<const float4*>(
-                    &sX0[stage * BM * PITCH + (wm * (BM / 2) + j * 32 + l32) * PITCH + kk * 8 + half * 4]);
+                    &sX0[stage * BM * PITCH + lds_at(wm * (BM / 2) + j * 32 + l32, kk * 2 + half)]);
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
@@ -248,21 +258,50 @@ static void launch_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st
     hipLaunchKernelGGL((gemm_kernel<T, BN, BM, ROWDW, PITCH>), dim3(grid), dim3(256), lds, st, a, sb, tiles_m, total);
 }
 
-// Tile choice (measured on MI355X at M = 512 / 1024 on the Llama2 shapes): fp32 is MFMA-issue
-// bound, so the only concern is filling 256 compute units; for half operands wide matrices
-// run best with 64-byte k steps and three or four workgroups per compute unit, while the
-// narrow ones (N = d_model) have few tiles and gain from 128-byte k steps (half the barriers).
+// Tile choice.  A compute unit holds `occ` workgroups of a variant at once and gets
+// ceil(tiles / 256) of them; what a variant achieves depends strongly on how many of its
+// workgroups are resident together (one alone cannot hide the latency of its own loads), so
+// the tail of a launch - the last n % occ tiles of a compute unit - runs at a lower rate.
+// rate[r-1] is the measured throughput (TFLOP/s, whole chip, Llama2 shapes at M = 512..4096)
+// with r workgroups resident per compute unit; the estimate below adds up full groups and the
+// tail and the cheapest variant is launched.
+struct GemmVariant {
+    int bn, bm, occ;
+    float rate[3];
+};
+
+static int pick_variant(const GemmVariant* v, int count, int M, int N) {
+    int best = 0;
+    double best_t = 0;
+    for (int c = 0; c < count; ++c) {
+        const long tiles = static_cast<long>((M + v[c].bm - 1) / v[c].bm) * ((N + v[c].bn - 1) / v[c].bn);
+        const long n = (tiles + 255) / 256;
+        const double w = static_cast<double>(v[c].bn) * v[c].bm;
+        const long tail = n % v[c].occ;
+        double t = static_cast<double>(n - tail) * w / v[c].rate[v[c].occ - 1];
+        if (tail) t += static_cast<double>(tail) * w / v[c].rate[tail - 1];
+        if (c == 0 || t < best_t) { best = c; best_t = t; }
+    }
+    return best;
+}
+
 static void launch_gemm_f32(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
-    const long t128 = static_cast<long>((a.M + 127) / 128) * ((a.N + 127) / 128);
-    if (t128 >= 512) launch_gemm<float, 128, 128, 16, 20>(a, sb, st);
-    else launch_gemm<float, 128, 64, 32, 36>(a, sb, st);  // few tiles: longer k steps, half the barriers
+    static const GemmVariant v[] = {{128, 128, 3, {108.f, 128.f, 133.f}}, {128, 64, 3, {101.f, 119.f, 125.f}}};
+    switch (pick_variant(v, 2, a.M, a.N)) {
+        case 0: launch_gemm<float, 128, 128, 16, 16>(a, sb, st); break;
+        default: launch_gemm<float, 128, 64, 32, 32>(a, sb, st); break;
+    }
 }
 
 static void launch_gemm_f16(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
-    const long t128 = static_cast<long>((a.M + 127) / 128) * ((a.N + 127) / 128);
-    if (t128 >= 700) launch_gemm<f16_t, 128, 128, 16, 20>(a, sb, st);
-    else if (t128 >= 256) launch_gemm<f16_t, 128, 128, 32, 36>(a, sb, st);
-    else launch_gemm<f16_t, 128, 64, 32, 36>(a, sb, st);
+    static const GemmVariant v[] = {{128, 128, 3, {390.f, 650.f, 850.f}},
+                                    {128, 128, 2, {470.f, 800.f, 0.f}},
+                                    {128, 64, 3, {270.f, 490.f, 700.f}}};
+    switch (pick_variant(v, 3, a.M, a.N)) {
+        case 0: launch_gemm<f16_t, 128, 128, 16, 16>(a, sb, st); break;
+        case 1: launch_gemm<f16_t, 128, 128, 32, 32>(a, sb, st); break;
+        default: launch_gemm<f16_t, 128, 64, 32, 32>(a, sb, st); break;
+    }
 }
 
 void launch_prefill_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
