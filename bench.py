@@ -12,7 +12,8 @@ inputs are resident in HBM before the timed region.  Prints one JSON line.
   prefill_tflops   algorithmic FLOPs of the prefill (projections + causal half of attention)
                    / time, and its fraction of the fp32 MFMA peak (157.3 TFLOP/s)
   roofline         the dominant kernel (the weight-streaming decode projection) from HIP
-                   events around each of its launches, in one extra instrumented step
+                   events attached to each of its dispatches (they read the kernel's own start
+                   and end, as a profiler's kernel trace does), in one extra instrumented step
   cpu_baseline     the float64 CPU oracle timed on a bounded sample of the same workload
 """
 from __future__ import annotations
@@ -169,14 +170,19 @@ def main():
     dec_gbps = work["decode_bytes"] * MB * n_dec * args.steps / t_dec / 1e9
     pre_tflops = work["prefill_flops"] * MB * args.steps / t_pre / 1e12
 
-    # one more step with HIP events around every launch, for the per-kernel roofline
+    # one more step with a HIP event pair on every dispatch, for the per-kernel roofline
     sh.timing_enable(True)
     one_step(False)
     kt = sh.timing_read()
     sh.timing_enable(False)
     proj = ("qkv", "o", "gateup", "down")
+    # passes over a projection's weights: one per layer call, except that batches the decode
+    # kernels cannot take at once (fp32 > 8 rows, half > 16) go in chunks of 8 rows
+    one_pass = B <= 8 or (wl["dtype"] != "f32" and B <= 16)
+    calls_dec = L * n_dec * MB * (1 if one_pass else -(-B // 8))
+    calls_pre = L * MB
     lin = {f: sum(kt["decode_" + k][f] for k in proj) for f in ("launches", "seconds")}
-    lin_bytes = sum(work["linear_bytes"].values()) * L * n_dec * MB
+    lin_bytes = sum(work["linear_bytes"].values()) * calls_dec
     lin_gbps = lin_bytes / lin["seconds"] / 1e9
     # HBM bytes per launch from rocprofv3 PMC runs of this same command (FETCH_SIZE and
     # WRITE_SIZE, scaled by what they read for a copy of known size); see profiles/
@@ -186,12 +192,15 @@ def main():
             traffic = json.load(fh)[args.workload]["decode_linear_kernel"]["traffic_bytes_per_launch"]
     except (OSError, KeyError, ValueError):
         pass
+    mfma_decode = wl["dtype"] != "f32" and 8 < B <= 16
+    n_lin = 4 * calls_dec                   # projection launches (the batched path's RMSNorm launches not counted)
     roofline = {
-        "kernel": "decode_linear_kernel (weight-streaming projections of shard_decode)",
+        "kernel": ("decode_linear_mfma_kernel" if mfma_decode else "decode_linear_kernel")
+                  + " (weight-streaming projections of shard_decode)",
         "bound": "hbm", "achieved": round(lin_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": round(lin_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
-        "launches": lin["launches"], "avg_launch_us": round(lin["seconds"] / max(1, lin["launches"]) * 1e6, 2),
-        "algorithmic_bytes_per_launch": round(lin_bytes / max(1, lin["launches"])),
+        "launches": n_lin, "avg_launch_us": round(lin["seconds"] / n_lin * 1e6, 2),
+        "algorithmic_bytes_per_launch": round(lin_bytes / n_lin),
     }
     gm = {f: sum(kt["prefill_" + k][f] for k in proj) for f in ("launches", "seconds")}
     gm_flops = sum(work["gemm_flops"].values()) * L * MB
@@ -206,9 +215,9 @@ def main():
                           "avg_us": round(v["seconds"] / max(1, v["launches"]) * 1e6, 2)} for k, v in kt.items()}
     for k in proj:      # per-projection rates of the two engines
         kernel_seconds["decode_" + k]["gbps"] = round(
-            work["linear_bytes"][k] * kt["decode_" + k]["launches"] / kt["decode_" + k]["seconds"] / 1e9, 1)
+            work["linear_bytes"][k] * calls_dec / kt["decode_" + k]["seconds"] / 1e9, 1)
         kernel_seconds["prefill_" + k]["tflops"] = round(
-            work["gemm_flops"][k] * kt["prefill_" + k]["launches"] / kt["prefill_" + k]["seconds"] / 1e12, 2)
+            work["gemm_flops"][k] * calls_pre / kt["prefill_" + k]["seconds"] / 1e12, 2)
     sh.close()
 
     out = {

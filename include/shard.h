@@ -153,10 +153,13 @@ int shard_decode(shard_t *s, const int32_t *seq_ids, int32_t B,
 int shard_profile(shard_t *s, int32_t B, int32_t T_prefill, int32_t n_decode, int32_t iters,
                   shard_layer_profile *out);
 
-/* Kernel timing for roofline reports.  While enabled, every kernel launch is bracketed by
- * HIP events on its stream; shard_timing_read waits for the stream work recorded so far
- * and returns launches and total seconds per class since enable.  The classes are the
- * steps of the layer, separately for the autoregressive and the prefill phase. */
+/* Kernel timing for roofline reports.  While enabled, every kernel dispatch carries a HIP
+ * event pair that reads the kernel's own start and end (no launch gaps, the figure a
+ * profiler's kernel trace gives); shard_timing_read waits for the stream work recorded so
+ * far and returns kernel launches and total kernel seconds per class since enable.  The
+ * classes are the steps of the layer, separately for the autoregressive and the prefill
+ * phase; a class may hold more than one kernel per layer (attention + its merge; the
+ * RMSNorm of the batched half-precision decode path counts with the projection it feeds). */
 enum {
     SHARD_K_DECODE_QKV = 0,     /* RMSNorm + QKV projection + RoPE + KV append */
     SHARD_K_DECODE_ATTN = 1,

@@ -178,7 +178,7 @@ __global__ __launch_bounds__(256) void decode_linear_kernel(DecodeLinear a, SeqB
 template <typename WT, int NB, int R, int U>
 static void launch_dl(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
     const int grid = (a.N + R - 1) / R;
-    hipLaunchKernelGGL((decode_linear_kernel<WT, NB, R, U>), dim3(grid), dim3(256), 0, st, a, sb);
+    launch((decode_linear_kernel<WT, NB, R, U>), dim3(grid), dim3(256), 0, st, a, sb);
 }
 
 // (rows per workgroup, chunks in flight) from a sweep on MI355X over the Llama2 shapes:
@@ -330,9 +330,9 @@ void launch_decode_linear_mfma(const DecodeLinear& a, const SeqBatch& sb, hipStr
     // (row tiles per workgroup, waves splitting K) from a sweep on the 70B shapes: more row
     // tiles re-use each activation fragment, more waves keep more loads in flight
     if (a.N >= 10240)
-        hipLaunchKernelGGL((decode_linear_mfma_kernel<4, 2, 16>), dim3((a.N + 63) / 64), dim3(1024), 0, st, a, sb);
+        launch((decode_linear_mfma_kernel<4, 2, 16>), dim3((a.N + 63) / 64), dim3(1024), 0, st, a, sb);
     else
-        hipLaunchKernelGGL((decode_linear_mfma_kernel<2, 2, 8>), dim3((a.N + 31) / 32), dim3(512), 0, st, a, sb);
+        launch((decode_linear_mfma_kernel<2, 2, 8>), dim3((a.N + 31) / 32), dim3(512), 0, st, a, sb);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -490,19 +490,19 @@ void launch_decode_attn(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st)
     const int units = a.nb * a.hq;
     switch (a.kv.dh) {
         case 32:
-            if (f32) hipLaunchKernelGGL((decode_attn_kernel<float, 32, 4>), grid, block, 0, st, a, sb);
-            else hipLaunchKernelGGL((decode_attn_kernel<f16_t, 32, 4>), grid, block, 0, st, a, sb);
-            if (a.nsplit > 1) hipLaunchKernelGGL(decode_attn_merge_kernel<32>, dim3(units), dim3(32), 0, st, a);
+            if (f32) launch((decode_attn_kernel<float, 32, 4>), grid, block, 0, st, a, sb);
+            else launch((decode_attn_kernel<f16_t, 32, 4>), grid, block, 0, st, a, sb);
+            if (a.nsplit > 1) launch(decode_attn_merge_kernel<32>, dim3(units), dim3(32), 0, st, a);
             break;
         case 64:
-            if (f32) hipLaunchKernelGGL((decode_attn_kernel<float, 64, 4>), grid, block, 0, st, a, sb);
-            else hipLaunchKernelGGL((decode_attn_kernel<f16_t, 64, 4>), grid, block, 0, st, a, sb);
-            if (a.nsplit > 1) hipLaunchKernelGGL(decode_attn_merge_kernel<64>, dim3(units), dim3(64), 0, st, a);
+            if (f32) launch((decode_attn_kernel<float, 64, 4>), grid, block, 0, st, a, sb);
+            else launch((decode_attn_kernel<f16_t, 64, 4>), grid, block, 0, st, a, sb);
+            if (a.nsplit > 1) launch(decode_attn_merge_kernel<64>, dim3(units), dim3(64), 0, st, a);
             break;
         default:
-            if (f32) hipLaunchKernelGGL((decode_attn_kernel<float, 128, 4>), grid, block, 0, st, a, sb);
-            else hipLaunchKernelGGL((decode_attn_kernel<f16_t, 128, 4>), grid, block, 0, st, a, sb);
-            if (a.nsplit > 1) hipLaunchKernelGGL(decode_attn_merge_kernel<128>, dim3(units), dim3(128), 0, st, a);
+            if (f32) launch((decode_attn_kernel<float, 128, 4>), grid, block, 0, st, a, sb);
+            else launch((decode_attn_kernel<f16_t, 128, 4>), grid, block, 0, st, a, sb);
+            if (a.nsplit > 1) launch(decode_attn_merge_kernel<128>, dim3(units), dim3(128), 0, st, a);
             break;
     }
 }
@@ -535,7 +535,7 @@ __global__ __launch_bounds__(256) void bf16_to_f16_kernel(uint16_t* buf, size_t 
 
 void launch_bf16_to_f16(void* buf, size_t n, uint32_t* overflow, hipStream_t st) {
     const size_t n8 = n / 8;  // matrices here have a multiple of 8 elements per row
-    hipLaunchKernelGGL(bf16_to_f16_kernel, dim3(static_cast<unsigned>((n8 + 255) / 256)), dim3(256), 0, st,
+    launch(bf16_to_f16_kernel, dim3(static_cast<unsigned>((n8 + 255) / 256)), dim3(256), 0, st,
                        static_cast<uint16_t*>(buf), n8, overflow);
 }
 
@@ -545,7 +545,7 @@ __global__ void table_update_kernel(int32_t* table, TableUpdate u) {
 }
 
 void launch_table_update(int32_t* table, const TableUpdate& u, hipStream_t st) {
-    hipLaunchKernelGGL(table_update_kernel, dim3(1), dim3(128), 0, st, table, u);
+    launch(table_update_kernel, dim3(1), dim3(128), 0, st, table, u);
 }
 
 }  // namespace shk

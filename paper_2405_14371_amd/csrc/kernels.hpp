@@ -2,6 +2,7 @@
 // the runtime (shard.cpp) checks shapes before it calls them.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "device_utils.hpp"
@@ -11,6 +12,25 @@ namespace shk {
 // Element types inside the library.  bf16 only exists at the boundary: shard_create converts
 // bf16 matrices to IEEE half once (launch_bf16_to_f16).
 enum DType { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };
+
+// Kernel timing.  While the runtime has a timer installed on the calling thread, every launch
+// asks it for a start/stop event pair and attaches the pair to its own dispatch, so the pair
+// reads the kernel's execution time (what a profiler's kernel trace reports) without the gap
+// between launches.  Without a timer the launch is an ordinary one.
+struct LaunchTimer {
+    bool (*next)(void* ctx, hipEvent_t* start, hipEvent_t* stop) = nullptr;
+    void* ctx = nullptr;
+};
+extern thread_local LaunchTimer g_launch_timer;  // defined by the runtime
+
+template <typename... P, typename... A>
+inline void launch(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds, hipStream_t st, A... args) {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (g_launch_timer.next && g_launch_timer.next(g_launch_timer.ctx, &e0, &e1))
+        hipExtLaunchKernelGGL(kernel, grid, block, static_cast<uint32_t>(lds), st, e0, e1, 0u, static_cast<P>(args)...);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, lds, st, static_cast<P>(args)...);
+}
 
 // One layer's paged KV cache.  Element (page p, kv head h, slot s, e) of K or V lives at
 // ((p * hkv + h) * page + s) * dh + e; token u of sequence q is in page

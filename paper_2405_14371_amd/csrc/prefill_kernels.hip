@@ -39,9 +39,9 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
 void launch_rmsnorm(const float* x, const float* gain, float eps, void* out, int32_t out_dtype,
                     int32_t M, int32_t d, hipStream_t st) {
     if (out_dtype == DT_F32)
-        hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(M), dim3(256), 0, st, x, gain, eps, static_cast<float*>(out), d);
+        launch(rmsnorm_kernel<float>, dim3(M), dim3(256), 0, st, x, gain, eps, static_cast<float*>(out), d);
     else
-        hipLaunchKernelGGL(rmsnorm_kernel<f16_t>, dim3(M), dim3(256), 0, st, x, gain, eps, static_cast<f16_t*>(out), d);
+        launch(rmsnorm_kernel<f16_t>, dim3(M), dim3(256), 0, st, x, gain, eps, static_cast<f16_t*>(out), d);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -255,7 +255,7 @@ static void launch_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st
                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         prepared = true;
     }
-    hipLaunchKernelGGL((gemm_kernel<T, BN, BM, ROWDW, PITCH>), dim3(grid), dim3(256), lds, st, a, sb, tiles_m, total);
+    launch((gemm_kernel<T, BN, BM, ROWDW, PITCH>), dim3(grid), dim3(256), lds, st, a, sb, tiles_m, total);
 }
 
 // Tile choice.  A compute unit holds `occ` workgroups of a variant at once and gets
@@ -548,9 +548,9 @@ template <typename OT>
 static void launch_pa_f16(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st) {
     const dim3 grid((a.T + 31) / 32, (a.hq + 3) / 4, a.B), block(256);
     switch (a.kv.dh) {
-        case 32: hipLaunchKernelGGL((prefill_attn_f16_kernel<OT, 32>), grid, block, 0, st, a, sb); break;
-        case 64: hipLaunchKernelGGL((prefill_attn_f16_kernel<OT, 64>), grid, block, 0, st, a, sb); break;
-        default: hipLaunchKernelGGL((prefill_attn_f16_kernel<OT, 128>), grid, block, 0, st, a, sb); break;
+        case 32: launch((prefill_attn_f16_kernel<OT, 32>), grid, block, 0, st, a, sb); break;
+        case 64: launch((prefill_attn_f16_kernel<OT, 64>), grid, block, 0, st, a, sb); break;
+        default: launch((prefill_attn_f16_kernel<OT, 128>), grid, block, 0, st, a, sb); break;
     }
 }
 
@@ -558,9 +558,9 @@ template <typename KT, typename OT>
 static void launch_pa(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st) {
     const dim3 grid((a.T + 31) / 32, (a.hq + 3) / 4, a.B), block(256);
     switch (a.kv.dh) {
-        case 32: hipLaunchKernelGGL((prefill_attn_kernel<KT, OT, 32>), grid, block, 0, st, a, sb); break;
-        case 64: hipLaunchKernelGGL((prefill_attn_kernel<KT, OT, 64>), grid, block, 0, st, a, sb); break;
-        default: hipLaunchKernelGGL((prefill_attn_kernel<KT, OT, 128>), grid, block, 0, st, a, sb); break;
+        case 32: launch((prefill_attn_kernel<KT, OT, 32>), grid, block, 0, st, a, sb); break;
+        case 64: launch((prefill_attn_kernel<KT, OT, 64>), grid, block, 0, st, a, sb); break;
+        default: launch((prefill_attn_kernel<KT, OT, 128>), grid, block, 0, st, a, sb); break;
     }
 }
 

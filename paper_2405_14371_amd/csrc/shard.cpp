@@ -18,6 +18,8 @@
 
 using namespace shk;
 
+thread_local shk::LaunchTimer shk::g_launch_timer;
+
 namespace {
 
 thread_local std::string g_err;
@@ -125,32 +127,35 @@ int validate_cfg(const shard_model_cfg* m, const shard_kv_cfg* kv, int lo, int h
     return SHARD_OK;
 }
 
-// start/stop event pair around one launch when timing is enabled
+// While alive and timing is enabled, every kernel launched on this thread is timed into `klass`.
 struct Bracket {
-    shard* s;
-    int klass;
-    hipStream_t st;
-    hipEvent_t stop = nullptr;
-    Bracket(shard* s_, int klass_, hipStream_t st_) : s(s_), klass(klass_), st(st_) {
-        Timing& t = s->timing;
-        if (!t.on) return;
-        auto& v = t.ev[klass];
-        if (t.used[klass] + 2 > v.size()) {
-            if (v.size() >= (1u << 16)) return;  // bounded; further launches go untimed
+    struct Ctx { shard* s; int klass; hipStream_t st; } ctx;
+    static bool next(void* p, hipEvent_t* start, hipEvent_t* stop) {
+        Ctx* c = static_cast<Ctx*>(p);
+        Timing& t = c->s->timing;
+        auto& v = t.ev[c->klass];
+        if (t.used[c->klass] + 2 > v.size()) {
+            if (v.size() >= (1u << 16)) return false;  // bounded; further launches go untimed
             hipEvent_t a, b;
-            if (hipEventCreate(&a) != hipSuccess) return;
-            if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+            if (hipEventCreate(&a) != hipSuccess) return false;
+            if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return false; }
             v.push_back(a);
             v.push_back(b);
         }
-        (void)hipEventRecord(v[t.used[klass]], st);
-        stop = v[t.used[klass] + 1];
-        t.used[klass] += 2;
-        t.last_stream = st;
+        *start = v[t.used[c->klass]];
+        *stop = v[t.used[c->klass] + 1];
+        t.used[c->klass] += 2;
+        t.last_stream = c->st;
+        return true;
     }
-    ~Bracket() {
-        if (stop) (void)hipEventRecord(stop, st);
+    Bracket(shard* s, int klass, hipStream_t st) : ctx{s, klass, st} {
+        if (!s->timing.on) return;
+        shk::g_launch_timer.next = &Bracket::next;
+        shk::g_launch_timer.ctx = &ctx;
     }
+    ~Bracket() { shk::g_launch_timer = shk::LaunchTimer{}; }
+    Bracket(const Bracket&) = delete;
+    Bracket& operator=(const Bracket&) = delete;
 };
 
 KvView kv_view(const shard* s, int li) {
