@@ -117,6 +117,25 @@ __device__ __forceinline__ void gemm_epilogue(const PrefillGemm& a, const SeqBat
 // a third of the LDS cycles at ROWDW = 16).
 // ---------------------------------------------------------------------------------------
 
+// Tile order.  Workgroups are dealt round-robin to the 8 XCDs (blockIdx % 8), each with its
+// own L2; every XCD gets a contiguous run of the tile sequence, and the sequence walks the
+// row tiles of a band of at most 8 before it moves to the next feature tile.  The workgroups
+// resident on an XCD at one time then form a block of about 8 x 4 tiles that shares its W
+// and its activation rows through that L2 (one feature tile at a time would re-stream all
+// activation rows from beyond the L2 for every feature tile once M is large).
+__device__ __forceinline__ bool tile_origin(int tiles_m, int tiles_total, int bn, int bm, int* n0, int* m0) {
+    const int per_xcd = (tiles_total + 7) / 8;
+    const int t = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (t >= tiles_total) return false;
+    const int tiles_n = tiles_total / tiles_m;
+    const int band = t / (8 * tiles_n), first_m = band * 8;
+    const int gm = min(tiles_m - first_m, 8);
+    const int r = t - band * 8 * tiles_n;
+    *m0 = (first_m + r % gm) * bm;
+    *n0 = (r / gm) * bn;
+    return true;
+}
+
 typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 
 template <typename T>
@@ -145,12 +164,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(PrefillGemm a, SeqBatch sb, i
     float* const sW0 = smem;                               // [2][BN * PITCH]
     float* const sX0 = smem + 2 * BN * PITCH;              // [2][BM * PITCH]
 
-    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
-    // tiles so that the workgroups sharing a W tile also share an L2.
-    const int per_xcd = (tiles_total + 7) / 8;
-    const int tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    if (tile >= tiles_total) return;
-    const int n0 = (tile / tiles_m) * BN, m0 = (tile % tiles_m) * BM;
+    int n0, m0;
+    if (!tile_origin(tiles_m, tiles_total, BN, BM, &n0, &m0)) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wn = wave >> 1, wm = wave & 1;
@@ -258,6 +273,146 @@ static void launch_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st
     launch((gemm_kernel<T, BN, BM, ROWDW, PITCH>), dim3(grid), dim3(256), lds, st, a, sb, tiles_m, total);
 }
 
+// ---------------------------------------------------------------------------------------
+// Half-precision GEMM with direct global->LDS loads (global_load_lds_dwordx4, gfx950) and a
+// ring of STAGES k-steps in LDS.  The register-staged kernel above keeps one k-step in
+// flight per workgroup; at the matrix cores' half-precision rate that is a fraction of the
+// bytes the memory latency asks for, and the counters show its waves waiting on their own
+// loads.  Here the loads of k-step ks + STAGES - 1 are issued while step ks is multiplied,
+// they occupy no registers, and one barrier per step both publishes a landed stage and
+// frees the one just consumed.
+// A wave-level load writes 64 lanes x 16 bytes to consecutive LDS addresses, i.e. 64/CH whole
+// rows of a stage; the XOR swizzle is applied on the global side (lane l fetches the chunk
+// that belongs in its LDS slot).  Rows past the matrix edge are clamped to the last row:
+// they feed accumulators that are never stored.  K must be a multiple of the k-step.
+// The loads are inline assembly because the compiler, for its own direct-to-LDS builtin,
+// waits for every outstanding load before any LDS read; waits here are explicit.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void lds_dma16(const void* g, uint32_t lds_byte) {
+    // lds_byte (wave-uniform) -> M0; lane l's 16 bytes land at lds_byte + 16 * l
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_byte) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int BN, int BM, int ROWDW, int STAGES, int WN, int WM>
+__global__ __launch_bounds__(64 * WN * WM) void gemm_dma_kernel(PrefillGemm a, SeqBatch sb, int tiles_m, int tiles_total) {
+    constexpr int NW = WN * WM;                  // waves per workgroup
+    constexpr int CH = ROWDW / 4;                // 16-byte chunks per row per step
+    constexpr int BK = CH * 8;                   // halfs of k per step
+    constexpr int TN = BN / WN / 32, TM = BM / WM / 32;  // MFMA tiles per wave
+    constexpr int RPC = 64 / CH;                 // rows per wave-level load (1 KB)
+    constexpr int NCW = BN / RPC, NCX = BM / RPC, NPER = (NCW + NCX) / NW;
+    constexpr int STAGE_DW = (BN + BM) * ROWDW;
+    static_assert((NCW + NCX) % NW == 0, "loads must divide evenly over the waves");
+    static_assert(NPER * (STAGES - 1) < 64, "vmcnt is a 6-bit counter");
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) void*)smem));
+
+    int n0, m0;
+    if (!tile_origin(tiles_m, tiles_total, BN, BM, &n0, &m0)) return;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wn = wave / WM, wm = wave % WM;
+    const int l32 = lane & 31, half = lane >> 5;
+    auto swz = [](int r) { return CH == 4 ? (r >> 2) & 3 : (r >> 1) & 7; };
+    auto lds_at = [&](int r, int c) { return r * ROWDW + ((c ^ swz(r)) << 2); };
+
+    const f16_t* __restrict__ W = static_cast<const f16_t*>(a.W);
+    const f16_t* __restrict__ X = static_cast<const f16_t*>(a.A);
+    const f16_t* src[NPER];
+    uint32_t dst[NPER];
+#pragma unroll
+    for (int i = 0; i < NPER; ++i) {
+        const int c = wave + NW * i;             // this wave's i-th load of a stage
+        const bool is_w = c < NCW;
+        const int cc = is_w ? c : c - NCW;
+        const int row = cc * RPC + lane / CH;
+        const int chunk = (lane % CH) ^ swz(row);
+        const int grow = is_w ? min(n0 + row, a.N - 1) : min(m0 + row, a.M - 1);
+        src[i] = (is_w ? W : X) + static_cast<size_t>(grow) * a.K + chunk * 8;
+        dst[i] = lds0 + (is_w ? 0 : BN * ROWDW * 4) + cc * 1024;
+    }
+    const int ksteps = a.K / BK;
+    auto issue = [&](int ks) {                   // k-step ks -> stage ks % STAGES
+        const int kc = ks < ksteps ? ks : ksteps - 1;   // past the end: a harmless reload into a free stage
+        const uint32_t sb0 = static_cast<uint32_t>(ks % STAGES) * (STAGE_DW * 4);
+#pragma unroll
+        for (int i = 0; i < NPER; ++i) lds_dma16(src[i] + static_cast<size_t>(kc) * BK, dst[i] + sb0);
+    };
+
+    f32x16 acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s) issue(s);
+    for (int ks = 0; ks < ksteps; ++ks) {
+        wait_vmcnt<NPER*(STAGES - 2)>();         // this wave's loads of step ks have landed
+        __syncthreads();                         // ... everyone's; and stage (ks-1) % STAGES is free
+        const float* sW = smem + (ks % STAGES) * STAGE_DW;
+        const float* sX = sW + BN * ROWDW;
+        // fragments of k-group kk+1 are fetched while the matrix cores work on group kk
+        float4 fw[2][TN], fx[2][TM];
+        auto fetch = [&](int kk, int buf) {
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+                fw[buf][i] = *reinterpret_cast<const float4*>(&sW[lds_at(wn * (BN / WN) + i * 32 + l32, kk * 2 + half)]);
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+                fx[buf][j] = *reinterpret_cast<const float4*>(&sX[lds_at(wm * (BM / WM) + j * 32 + l32, kk * 2 + half)]);
+        };
+        fetch(0, 0);
+        issue(ks + STAGES - 1);                  // issued under the latency of the first fetch
+#pragma unroll
+        for (int kk = 0; kk < ROWDW / 8; ++kk) {
+            if (kk + 1 < ROWDW / 8) fetch(kk + 1, (kk + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);   // keep the fetch ahead of the multiplies
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int j = 0; j < TM; ++j) mfma_chunk<f16_t>(fw[kk & 1][i], fx[kk & 1][j], acc[i][j]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    wait_vmcnt<0>();                             // the reloads past the end
+
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const int n4 = n0 + wn * (BN / WN) + i * 32 + vq * 8 + half * 4;
+                const int m = m0 + wm * (BM / WM) + j * 32 + l32;
+                const float val[4] = {acc[i][j][vq * 4], acc[i][j][vq * 4 + 1], acc[i][j][vq * 4 + 2], acc[i][j][vq * 4 + 3]};
+                gemm_epilogue<f16_t>(a, sb, m, n4, val);
+            }
+}
+
+template <int BN, int BM, int ROWDW, int STAGES, int WN, int WM>
+static void launch_gemm_dma(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
+    const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+    const int total = tiles_m * tiles_n;
+    const int grid = ((total + 7) / 8) * 8;
+    constexpr size_t lds = static_cast<size_t>(STAGES) * (BN + BM) * ROWDW * sizeof(float);
+    static_assert(lds <= 160 * 1024, "LDS of a compute unit");
+    static bool prepared = false;
+    if (!prepared) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_dma_kernel<BN, BM, ROWDW, STAGES, WN, WM>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        prepared = true;
+    }
+    launch(gemm_dma_kernel<BN, BM, ROWDW, STAGES, WN, WM>, dim3(grid), dim3(64 * WN * WM), lds, st, a, sb, tiles_m, total);
+}
+
 // Tile choice.  A compute unit holds `occ` workgroups of a variant at once and gets
 // ceil(tiles / 256) of them; what a variant achieves depends strongly on how many of its
 // workgroups are resident together (one alone cannot hide the latency of its own loads), so
@@ -294,6 +449,19 @@ static void launch_gemm_f32(const PrefillGemm& a, const SeqBatch& sb, hipStream_
 }
 
 static void launch_gemm_f16(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
+    if (a.K % 64 == 0) {  // direct-to-LDS variants (k-step of 64)
+        static const GemmVariant v[] = {{256, 256, 1, {1500.f, 0.f, 0.f}},
+                                        {256, 128, 1, {1250.f, 0.f, 0.f}},
+                                        {128, 128, 1, {1000.f, 0.f, 0.f}},
+                                        {128, 64, 2, {650.f, 900.f, 0.f}}};
+        switch (pick_variant(v, 4, a.M, a.N)) {
+            case 0: launch_gemm_dma<256, 256, 32, 2, 4, 2>(a, sb, st); break;
+            case 1: launch_gemm_dma<256, 128, 32, 3, 4, 2>(a, sb, st); break;
+            case 2: launch_gemm_dma<128, 128, 32, 3, 2, 2>(a, sb, st); break;
+            default: launch_gemm_dma<128, 64, 32, 3, 2, 2>(a, sb, st); break;
+        }
+        return;
+    }
     static const GemmVariant v[] = {{128, 128, 3, {390.f, 650.f, 850.f}},
                                     {128, 128, 2, {470.f, 800.f, 0.f}},
                                     {128, 64, 3, {270.f, 490.f, 700.f}}};
