@@ -77,7 +77,8 @@ typedef struct {
 typedef struct {
     int32_t max_seqs;         /* sequences that can be live at once (>= 1) */
     int32_t max_seq_len;      /* tokens per sequence the cache can hold (>= 1) */
-    int32_t page_size;        /* tokens per KV page (>= 1; 16 is the tuned value) */
+    int32_t page_size;        /* tokens per KV page (>= 1; 16 is the tuned value);
+                                 max_seq_len * page_size must be below 2^32 */
     int32_t max_batch_tokens; /* largest B*T of one shard_prefill call; 0 = max_seq_len */
 } shard_kv_cfg;
 

@@ -156,8 +156,7 @@ __global__ __launch_bounds__(256) void decode_linear_kernel(DecodeLinear a, SeqB
             return;
         }
         const int hk = (n0 - nq) / dh;
-        const int page = a.kv.block_table[sb.seq[b] * a.kv.max_pages + pos / a.kv.page];
-        const size_t at = ((static_cast<size_t>(page) * a.kv.hkv + hk) * a.kv.page + pos % a.kv.page) * dh + e;
+        const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
         typedef typename ActOf<WT>::type CT;  // cache element type
         CT* kp = static_cast<CT*>(a.kv.k);
         kp[at] = Elem<CT>::from_f32(r0);
@@ -167,8 +166,7 @@ __global__ __launch_bounds__(256) void decode_linear_kernel(DecodeLinear a, SeqB
     {
         typedef typename ActOf<WT>::type CT;
         const int hk = (n0 - nq - nk) / dh, e = n0 % dh;
-        const int page = a.kv.block_table[sb.seq[b] * a.kv.max_pages + pos / a.kv.page];
-        const size_t at = ((static_cast<size_t>(page) * a.kv.hkv + hk) * a.kv.page + pos % a.kv.page) * dh + e;
+        const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
         CT* vp = static_cast<CT*>(a.kv.v);
         vp[at] = Elem<CT>::from_f32(v0);
         vp[at + 1] = Elem<CT>::from_f32(v1);
@@ -226,6 +224,10 @@ __global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLi
     const f16_t* __restrict__ W = static_cast<const f16_t*>(a.W);
     const f16_t* __restrict__ X = static_cast<const f16_t*>(a.xb);
     const int K = a.K, nblk = K / 64;  // K is a multiple of 64 on this path
+    // Every workgroup walks K from its own starting block.  Workgroups of one launch run in
+    // lockstep, and with rows a power of two apart they would all ask the same few memory
+    // channels for the same k offset at the same time (measured: 4.8 -> 6.1 TB/s at K = 8192).
+    const int rot = static_cast<int>((blockIdx.x * 37u) % static_cast<unsigned>(nblk));
 
     const f16_t* wp[TILES];
 #pragma unroll
@@ -243,7 +245,8 @@ __global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLi
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int kb = kb0 + WAVES * u;
-            const int kc = kb < nblk ? kb : kb0;  // past the end: re-read a valid block, zero its activations
+            int kc = (kb < nblk ? kb : kb0) + rot;  // past the end: re-read a valid block, zero its activations
+            if (kc >= nblk) kc -= nblk;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
 #pragma unroll
@@ -289,7 +292,8 @@ __global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLi
         return;
     }
     // pair epilogues: thread -> (row pair j, activation row b)
-    if (tid >= ROWS * 8) return;   // ROWS/2 row pairs x 16 activation rows (needs THREADS >= ROWS*8)
+    static_assert(THREADS >= ROWS * 8, "one thread per (row pair, activation row)");
+    if (tid >= ROWS * 8) return;   // ROWS/2 row pairs x 16 activation rows
     const int j = tid >> 4, b = tid & 15;
     const int n0 = row0 + 2 * j;
     if (n0 >= a.N || b >= a.nb) return;
@@ -311,16 +315,14 @@ __global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLi
             return;
         }
         const int hk = (n0 - nq) / dh;
-        const int page = a.kv.block_table[sb.seq[b] * a.kv.max_pages + pos / a.kv.page];
-        const size_t at = ((static_cast<size_t>(page) * a.kv.hkv + hk) * a.kv.page + pos % a.kv.page) * dh + e;
+        const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
         f16_t* kp = static_cast<f16_t*>(a.kv.k);
         kp[at] = static_cast<f16_t>(r0);
         kp[at + 1] = static_cast<f16_t>(r1);
         return;
     }
     const int hk = (n0 - nq - nk) / dh;
-    const int page = a.kv.block_table[sb.seq[b] * a.kv.max_pages + pos / a.kv.page];
-    const size_t at = ((static_cast<size_t>(page) * a.kv.hkv + hk) * a.kv.page + pos % a.kv.page) * dh + e;
+    const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
     f16_t* vp = static_cast<f16_t*>(a.kv.v);
     vp[at] = static_cast<f16_t>(v0);
     vp[at + 1] = static_cast<f16_t>(v1);
@@ -328,11 +330,11 @@ __global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLi
 
 void launch_decode_linear_mfma(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
     // (row tiles per workgroup, waves splitting K) from a sweep on the 70B shapes: more row
-    // tiles re-use each activation fragment, more waves keep more loads in flight
+    // tiles re-use each activation fragment, but the launch has to cover 256 compute units
     if (a.N >= 10240)
-        launch((decode_linear_mfma_kernel<4, 2, 16>), dim3((a.N + 63) / 64), dim3(1024), 0, st, a, sb);
+        launch((decode_linear_mfma_kernel<4, 2, 8>), dim3((a.N + 63) / 64), dim3(512), 0, st, a, sb);
     else
-        launch((decode_linear_mfma_kernel<2, 2, 8>), dim3((a.N + 31) / 32), dim3(512), 0, st, a, sb);
+        launch((decode_linear_mfma_kernel<2, 2, 4>), dim3((a.N + 31) / 32), dim3(256), 0, st, a, sb);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -384,8 +386,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttn a, SeqBatch
             const int u = u0 + i * GROUPS;
             ok[i] = u < u_end;
             const int uc = ok[i] ? u : u0;
-            const int page = bt[uc / a.kv.page];
-            const size_t at = ((static_cast<size_t>(page) * a.kv.hkv + hk) * a.kv.page + uc % a.kv.page) * DH + e0;
+            const size_t at = kv_row_div(a.kv, bt, uc, hk) * DH + e0;
             kv[i].load(kp + at);
             vv[i].load(vp + at);
         }

@@ -40,7 +40,28 @@ struct KvView {
     void* v;
     const int32_t* block_table;
     int32_t max_pages, page, hkv, dh;
+    uint32_t page_magic;   // ceil(2^32 / page) for page >= 2: u / page == mulhi(u, page_magic) while u * page < 2^32
 };
+
+// Page number and slot of token position u, without an integer division.
+__device__ __forceinline__ void kv_split(const KvView& kv, int u, int* pg, int* slot) {
+    const uint32_t q = kv.page == 1 ? static_cast<uint32_t>(u) : __umulhi(static_cast<uint32_t>(u), kv.page_magic);
+    *pg = static_cast<int>(q);
+    *slot = u - static_cast<int>(q) * kv.page;
+}
+// Row (in units of dh elements) of token u of the sequence whose block-table row is bt, kv head hk.
+// Two forms of the same index: kv_row finds the page with a multiply-high, kv_row_div with the
+// compiler's division sequence.  Which one is faster depends on the kernel around it (the
+// division's longer address computation happens to be scheduled further ahead of the loads
+// that need it); each kernel uses the form that measured faster.
+__device__ __forceinline__ size_t kv_row_div(const KvView& kv, const int32_t* bt, int u, int hk) {
+    return (static_cast<size_t>(bt[u / kv.page]) * kv.hkv + hk) * kv.page + u % kv.page;
+}
+__device__ __forceinline__ size_t kv_row(const KvView& kv, const int32_t* bt, int u, int hk) {
+    int pg, slot;
+    kv_split(kv, u, &pg, &slot);
+    return (static_cast<size_t>(bt[pg]) * kv.hkv + hk) * kv.page + slot;
+}
 
 enum Epilogue {
     EPI_QKV = 0,     // RoPE on q,k; q -> q buffer (fp32); k,v -> cache pages

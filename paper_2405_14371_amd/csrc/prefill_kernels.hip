@@ -90,8 +90,7 @@ __device__ __forceinline__ void gemm_epilogue(const PrefillGemm& a, const SeqBat
     }
     const bool is_k = n4 < nq + nk;
     const int hk = (n4 - nq - (is_k ? 0 : nk)) / dh;
-    const int page = a.kv.block_table[sb.seq[b] * a.kv.max_pages + pos / a.kv.page];
-    const size_t at = ((static_cast<size_t>(page) * a.kv.hkv + hk) * a.kv.page + pos % a.kv.page) * dh + e;
+    const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
     ET* dst = static_cast<ET*>(is_k ? a.kv.k : a.kv.v) + at;
 #pragma unroll
     for (int i = 0; i < 4; ++i) dst[i] = Elem<ET>::from_f32(r[i]);
@@ -274,7 +273,7 @@ static void launch_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st
 }
 
 // ---------------------------------------------------------------------------------------
-// Half-precision GEMM with direct global->LDS loads (global_load_lds_dwordx4, gfx950) and a
+// GEMM with direct global->LDS loads (global_load_lds_dwordx4, gfx950) and a
 // ring of STAGES k-steps in LDS.  The register-staged kernel above keeps one k-step in
 // flight per workgroup; at the matrix cores' half-precision rate that is a fraction of the
 // bytes the memory latency asks for, and the counters show its waves waiting on their own
@@ -297,11 +296,12 @@ __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int BN, int BM, int ROWDW, int STAGES, int WN, int WM>
+template <typename T, int BN, int BM, int ROWDW, int STAGES, int WN, int WM>
 __global__ __launch_bounds__(64 * WN * WM) void gemm_dma_kernel(PrefillGemm a, SeqBatch sb, int tiles_m, int tiles_total) {
     constexpr int NW = WN * WM;                  // waves per workgroup
     constexpr int CH = ROWDW / 4;                // 16-byte chunks per row per step
-    constexpr int BK = CH * 8;                   // halfs of k per step
+    constexpr int VEC = Elem<T>::VEC;            // elements per 16 bytes
+    constexpr int BK = CH * VEC;                 // elements of k per step
     constexpr int TN = BN / WN / 32, TM = BM / WM / 32;  // MFMA tiles per wave
     constexpr int RPC = 64 / CH;                 // rows per wave-level load (1 KB)
     constexpr int NCW = BN / RPC, NCX = BM / RPC, NPER = (NCW + NCX) / NW;
@@ -321,9 +321,10 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_dma_kernel(PrefillGemm a, S
     auto swz = [](int r) { return CH == 4 ? (r >> 2) & 3 : (r >> 1) & 7; };
     auto lds_at = [&](int r, int c) { return r * ROWDW + ((c ^ swz(r)) << 2); };
 
-    const f16_t* __restrict__ W = static_cast<const f16_t*>(a.W);
-    const f16_t* __restrict__ X = static_cast<const f16_t*>(a.A);
-    const f16_t* src[NPER];
+    typedef typename ActOf<T>::type AT;          // activation type (same size as T)
+    const T* __restrict__ W = static_cast<const T*>(a.W);
+    const T* __restrict__ X = static_cast<const T*>(a.A);
+    const T* src[NPER];
     uint32_t dst[NPER];
 #pragma unroll
     for (int i = 0; i < NPER; ++i) {
@@ -333,7 +334,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_dma_kernel(PrefillGemm a, S
         const int row = cc * RPC + lane / CH;
         const int chunk = (lane % CH) ^ swz(row);
         const int grow = is_w ? min(n0 + row, a.N - 1) : min(m0 + row, a.M - 1);
-        src[i] = (is_w ? W : X) + static_cast<size_t>(grow) * a.K + chunk * 8;
+        src[i] = (is_w ? W : X) + static_cast<size_t>(grow) * a.K + chunk * VEC;
         dst[i] = lds0 + (is_w ? 0 : BN * ROWDW * 4) + cc * 1024;
     }
     const int ksteps = a.K / BK;
@@ -378,7 +379,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_dma_kernel(PrefillGemm a, S
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
-                for (int j = 0; j < TM; ++j) mfma_chunk<f16_t>(fw[kk & 1][i], fx[kk & 1][j], acc[i][j]);
+                for (int j = 0; j < TM; ++j) mfma_chunk<T>(fw[kk & 1][i], fx[kk & 1][j], acc[i][j]);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -393,11 +394,11 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_dma_kernel(PrefillGemm a, S
                 const int n4 = n0 + wn * (BN / WN) + i * 32 + vq * 8 + half * 4;
                 const int m = m0 + wm * (BM / WM) + j * 32 + l32;
                 const float val[4] = {acc[i][j][vq * 4], acc[i][j][vq * 4 + 1], acc[i][j][vq * 4 + 2], acc[i][j][vq * 4 + 3]};
-                gemm_epilogue<f16_t>(a, sb, m, n4, val);
+                gemm_epilogue<AT>(a, sb, m, n4, val);
             }
 }
 
-template <int BN, int BM, int ROWDW, int STAGES, int WN, int WM>
+template <typename T, int BN, int BM, int ROWDW, int STAGES, int WN, int WM>
 static void launch_gemm_dma(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
     const int total = tiles_m * tiles_n;
@@ -406,11 +407,11 @@ static void launch_gemm_dma(const PrefillGemm& a, const SeqBatch& sb, hipStream_
     static_assert(lds <= 160 * 1024, "LDS of a compute unit");
     static bool prepared = false;
     if (!prepared) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_dma_kernel<BN, BM, ROWDW, STAGES, WN, WM>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_dma_kernel<T, BN, BM, ROWDW, STAGES, WN, WM>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         prepared = true;
     }
-    launch(gemm_dma_kernel<BN, BM, ROWDW, STAGES, WN, WM>, dim3(grid), dim3(64 * WN * WM), lds, st, a, sb, tiles_m, total);
+    launch(gemm_dma_kernel<T, BN, BM, ROWDW, STAGES, WN, WM>, dim3(grid), dim3(64 * WN * WM), lds, st, a, sb, tiles_m, total);
 }
 
 // Tile choice.  A compute unit holds `occ` workgroups of a variant at once and gets
@@ -441,6 +442,17 @@ static int pick_variant(const GemmVariant* v, int count, int M, int N) {
 }
 
 static void launch_gemm_f32(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
+    if (a.K % 16 == 0) {  // direct-to-LDS variants (k-step of 16 or 32)
+        static const GemmVariant v[] = {{128, 128, 2, {100.f, 142.f, 0.f}},
+                                        {128, 64, 3, {125.f, 120.f, 116.f}},
+                                        {128, 64, 2, {116.f, 131.f, 0.f}}};
+        switch (pick_variant(v, a.K % 32 == 0 ? 3 : 2, a.M, a.N)) {
+            case 0: launch_gemm_dma<float, 128, 128, 16, 4, 2, 2>(a, sb, st); break;
+            case 1: launch_gemm_dma<float, 128, 64, 16, 4, 2, 2>(a, sb, st); break;
+            default: launch_gemm_dma<float, 128, 64, 32, 3, 2, 2>(a, sb, st); break;
+        }
+        return;
+    }
     static const GemmVariant v[] = {{128, 128, 3, {108.f, 128.f, 133.f}}, {128, 64, 3, {101.f, 119.f, 125.f}}};
     switch (pick_variant(v, 2, a.M, a.N)) {
         case 0: launch_gemm<float, 128, 128, 16, 16>(a, sb, st); break;
@@ -455,10 +467,10 @@ static void launch_gemm_f16(const PrefillGemm& a, const SeqBatch& sb, hipStream_
                                         {128, 128, 1, {1000.f, 0.f, 0.f}},
                                         {128, 64, 2, {650.f, 900.f, 0.f}}};
         switch (pick_variant(v, 4, a.M, a.N)) {
-            case 0: launch_gemm_dma<256, 256, 32, 2, 4, 2>(a, sb, st); break;
-            case 1: launch_gemm_dma<256, 128, 32, 3, 4, 2>(a, sb, st); break;
-            case 2: launch_gemm_dma<128, 128, 32, 3, 2, 2>(a, sb, st); break;
-            default: launch_gemm_dma<128, 64, 32, 3, 2, 2>(a, sb, st); break;
+            case 0: launch_gemm_dma<f16_t, 256, 256, 32, 2, 4, 2>(a, sb, st); break;
+            case 1: launch_gemm_dma<f16_t, 256, 128, 32, 3, 4, 2>(a, sb, st); break;
+            case 2: launch_gemm_dma<f16_t, 128, 128, 32, 3, 2, 2>(a, sb, st); break;
+            default: launch_gemm_dma<f16_t, 128, 64, 32, 3, 2, 2>(a, sb, st); break;
         }
         return;
     }
@@ -535,7 +547,7 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(PrefillAttn a, SeqBat
     for (int k0 = 0; k0 <= last_key; k0 += 32) {
         // S^T tile
         const int u = min(k0 + l32, ctx - 1);
-        const size_t kat = ((static_cast<size_t>(bt[u / page]) * hkv + hk) * page + u % page) * DH + half * 4;
+        const size_t kat = kv_row_div(a.kv, bt, u, hk) * DH + half * 4;
         f32x16 s;
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[v] = 0.f;
@@ -577,7 +589,7 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(PrefillAttn a, SeqBat
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int key = min(k0 + (v >> 2) * 8 + half * 4 + (v & 3), ctx - 1);
-            const size_t vat = ((static_cast<size_t>(bt[key / page]) * hkv + hk) * page + key % page) * DH + l32;
+            const size_t vat = kv_row_div(a.kv, bt, key, hk) * DH + l32;
 #pragma unroll
             for (int j = 0; j < DH / 32; ++j) {
                 const float vv = Elem<KT>::to_f32(vp[vat + j * 32]);
@@ -645,7 +657,7 @@ __global__ __launch_bounds__(256) void prefill_attn_f16_kernel(PrefillAttn a, Se
 
     for (int k0 = 0; k0 <= last_key; k0 += 32) {
         const int u = min(k0 + l32, ctx - 1);
-        const size_t kat = ((static_cast<size_t>(bt[u / page]) * hkv + hk) * page + u % page) * DH + half * 8;
+        const size_t kat = kv_row(a.kv, bt, u, hk) * DH + half * 8;
         f32x16 s;
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[v] = 0.f;
@@ -687,7 +699,7 @@ __global__ __launch_bounds__(256) void prefill_attn_f16_kernel(PrefillAttn a, Se
                 pf[i] = static_cast<f16_t>(s[mm * 8 + i]);
                 // register 8*mm + i of this lane is key 16*mm + 8*(i/4) + 4*half + i%4
                 const int key = min(k0 + mm * 16 + (i >> 2) * 8 + half * 4 + (i & 3), ctx - 1);
-                vat[i] = ((static_cast<size_t>(bt[key / page]) * hkv + hk) * page + key % page) * DH + l32;
+                vat[i] = kv_row(a.kv, bt, key, hk) * DH + l32;
             }
 #pragma unroll
             for (int j = 0; j < DH / 32; ++j) {

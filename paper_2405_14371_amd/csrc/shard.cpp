@@ -124,6 +124,8 @@ int validate_cfg(const shard_model_cfg* m, const shard_kv_cfg* kv, int lo, int h
     if (!(m->rms_eps >= 0.f) || !(m->rope_theta > 0.f)) return fail(SHARD_E_INVAL, "bad rms_eps / rope_theta");
     if (kv->max_seqs < 1 || kv->max_seq_len < 1 || kv->page_size < 1 || kv->max_batch_tokens < 0)
         return fail(SHARD_E_INVAL, "bad KV configuration");
+    if (static_cast<uint64_t>(kv->max_seq_len) * static_cast<uint64_t>(kv->page_size) >= (1ull << 32))
+        return fail(SHARD_E_INVAL, "max_seq_len * page_size must be below 2^32");
     return SHARD_OK;
 }
 
@@ -167,6 +169,7 @@ KvView kv_view(const shard* s, int li) {
     v.page = s->kv.page_size;
     v.hkv = s->m.n_kv_heads;
     v.dh = s->m.head_dim;
+    v.page_magic = v.page >= 2 ? static_cast<uint32_t>(((1ull << 32) + v.page - 1) / v.page) : 0u;
     return v;
 }
 

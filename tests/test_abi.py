@@ -77,6 +77,27 @@ def test_create_rejects_bad_ranges_and_nulls(lib):
     assert rc == lib.SHARD_E_INVAL and "null tensor" in msg
 
 
+def test_page_index_by_multiply_high_is_exact():
+    """The kernels find a token's page as mulhi(u, ceil(2^32 / page)); that equals u // page
+    for every position the library admits (u * page < 2^32, enforced at create)."""
+    import random
+    rng = random.Random(7)
+    for page in list(range(2, 70)) + [127, 128, 129, 1000, 4096, 65535, 65536]:
+        magic = ((1 << 32) + page - 1) // page
+        assert magic < (1 << 32)
+        lim = (1 << 32) // page
+        us = [0, 1, page - 1, page, page + 1] + [lim - 1 - i for i in range(min(lim, 500))]
+        us += [rng.randrange(lim) for _ in range(500)] + [k * page - 1 for k in range(1, 40) if k * page - 1 < lim]
+        for u in us:
+            assert (u * magic) >> 32 == u // page, (u, page)
+
+
+def test_create_rejects_positions_beyond_the_page_index_range(lib):
+    mc = lib.ModelCfg(**GOOD)
+    rc, msg = _create(lib, mc, lib.KvCfg(1, 1 << 30, 16, 0))
+    assert rc == lib.SHARD_E_INVAL and "2^32" in msg
+
+
 def test_null_handles_are_errors_not_crashes(lib):
     h = lib.load()
     ids = (C.c_int32 * 1)(0)
