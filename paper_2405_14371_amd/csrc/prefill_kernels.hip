@@ -744,7 +744,289 @@ static void launch_pa(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st) 
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Prefill attention with key/value tiles staged in LDS (head_dim 64 or 128).
+// A workgroup owns 128 consecutive query rows of one (sequence, head): QT = 4 waves take one
+// 32-row query tile each, and KS groups of such waves split the 32-key blocks between them
+// (group g takes blocks g, g + KS, ...), each with its own running max / sum / output, merged
+// at the end in group order.  The waves of a group share every K and V tile: the tile is
+// fetched once, straight from global memory into a ring of LDS stages (16 bytes per lane,
+// addresses from the sequence's block-table row, which is copied to LDS first), the fetch of
+// block i + STAGES - 1 in flight while block i is multiplied.  The kernels above instead read
+// K and V per wave from global memory and, for V^T, element by element.
+// LDS rows are whole K / V rows; 16-byte chunks are XOR-swizzled so that the 16-byte K
+// fragment reads (one row per lane) and the element reads of V^T (rows 4 apart in the two
+// half-waves) do not collide on banks.
+// Same arithmetic as the kernels above: S^T = K Q^T and O^T = V^T P^T on the matrix cores,
+// softmax per query column in fp32.
+// ---------------------------------------------------------------------------------------
+template <typename KT, int DH, int KS, int STAGES>
+__global__ __launch_bounds__(256 * KS) void prefill_attn_lds_kernel(PrefillAttn a, SeqBatch sb) {
+    constexpr int QT = 4;
+    constexpr bool F16 = sizeof(KT) == 2;
+    constexpr int VEC = 16 / sizeof(KT);
+    constexpr int CHR = DH / VEC;                 // 16-byte chunks per row
+    constexpr int RPI = 64 / CHR;                 // rows per wave-level load
+    constexpr int ROWB = DH * sizeof(KT);         // bytes per row
+    constexpr int TILE_B = 32 * ROWB;             // one K or V tile
+    constexpr int STAGE_B = 2 * TILE_B;
+    constexpr int NPER = 2 * 32 / RPI / QT;       // loads per wave per stage
+    constexpr int BT_CAP = 2048;                  // block-table entries cached in LDS (the launcher checks the context fits)
+    static_assert(CHR >= 8 && (2 * 32 / RPI) % QT == 0, "head_dim 64 or 128");
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    int32_t* s_bt = reinterpret_cast<int32_t*>(lds);
+    char* ring = lds + BT_CAP * 4;
+    const uint32_t ring0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) void*)ring));
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wq = wave % QT, g = wave / QT;      // query tile in the block, key-split group
+    const int l32 = lane & 31, half = lane >> 5;
+    const int qg = gridDim.x - 1 - blockIdx.x;    // longest rows first
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int hk = h / (a.hq / a.kv.hkv);
+    const int P = sb.pos[b];
+    const int ctx = P + a.T;
+    const int32_t* bt = a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages;
+    const KT* __restrict__ kp = static_cast<const KT*>(a.kv.k);
+    const KT* __restrict__ vp = static_cast<const KT*>(a.kv.v);
+
+    // blocks this workgroup walks: up to the diagonal of its last query row
+    const int last_row_wg = min(qg * 128 + 127, a.T - 1);
+    const int nblk_wg = (P + last_row_wg) / 32 + 1;
+    const int steps = (nblk_wg + KS - 1) / KS;
+    const int npages = (ctx - 1) / a.kv.page + 1;
+    for (int i = tid; i < npages; i += 256 * KS) s_bt[i] = bt[i];
+    __syncthreads();
+
+    // this lane's share of a stage: NPER loads, each 16 bytes of one K or V row
+    auto swz_k = [](int r) { return CHR >= 16 ? (r & 15) : ((r >> 1) & 7); };
+    auto swz_v = [](int r) { return ((r >> 2) & 1) * (F16 ? 4 : 8); };
+    int ld_row[NPER], ld_chunk[NPER];
+    bool ld_isv[NPER];
+#pragma unroll
+    for (int i = 0; i < NPER; ++i) {
+        const int c = wq + QT * i;                // this wave's i-th load of its group's stage
+        constexpr int PER_TILE = 32 / RPI;
+        ld_isv[i] = c >= PER_TILE;
+        const int cc = ld_isv[i] ? c - PER_TILE : c;
+        ld_row[i] = cc * RPI + lane / CHR;
+        ld_chunk[i] = (lane % CHR) ^ (ld_isv[i] ? swz_v(ld_row[i]) : swz_k(ld_row[i]));
+    }
+    auto issue = [&](int step) {                  // block (step * KS + g) -> stage step % STAGES of group g
+        int kb = step * KS + g;
+        if (kb >= nblk_wg) kb = nblk_wg - 1;      // past the end: a harmless reload
+        const uint32_t st0 = ring0 + (static_cast<uint32_t>(g) * STAGES + step % STAGES) * STAGE_B;
+#pragma unroll
+        for (int i = 0; i < NPER; ++i) {
+            const int u = min(kb * 32 + ld_row[i], ctx - 1);
+            int pg, slot;
+            kv_split(a.kv, u, &pg, &slot);
+            const size_t row = (static_cast<size_t>(s_bt[pg]) * a.kv.hkv + hk) * a.kv.page + slot;
+            const KT* src = (ld_isv[i] ? vp : kp) + row * DH + ld_chunk[i] * VEC;
+            const int c = wq + QT * i;
+            lds_dma16(src, st0 + (ld_isv[i] ? TILE_B : 0) + (ld_isv[i] ? c - 32 / RPI : c) * 1024);
+        }
+    };
+
+    // query fragments (scaled), this wave's 32 rows
+    const int t_q = qg * 128 + wq * 32 + l32;
+    const int t_ld = min(t_q, a.T - 1);
+    const size_t qrow = (static_cast<size_t>(b) * a.T + t_ld) * a.hq * DH + h * DH;
+    const float scale = 1.0f / sqrtf(static_cast<float>(DH));
+    float4 qf[DH / 8];                            // fp32: 4 floats per k-group of 8; half: 8 halfs per k-group of 16
+    if constexpr (F16) {
+#pragma unroll
+        for (int j = 0; j < DH / 16; ++j) {
+            const float4 lo = *reinterpret_cast<const float4*>(a.q + qrow + j * 16 + half * 8);
+            const float4 hi = *reinterpret_cast<const float4*>(a.q + qrow + j * 16 + half * 8 + 4);
+            f16x8_t t;
+            t[0] = static_cast<f16_t>(lo.x * scale); t[1] = static_cast<f16_t>(lo.y * scale);
+            t[2] = static_cast<f16_t>(lo.z * scale); t[3] = static_cast<f16_t>(lo.w * scale);
+            t[4] = static_cast<f16_t>(hi.x * scale); t[5] = static_cast<f16_t>(hi.y * scale);
+            t[6] = static_cast<f16_t>(hi.z * scale); t[7] = static_cast<f16_t>(hi.w * scale);
+            qf[j] = __builtin_bit_cast(float4, t);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < DH / 8; ++j) {
+            qf[j] = *reinterpret_cast<const float4*>(a.q + qrow + j * 8 + half * 4);
+            qf[j].x *= scale; qf[j].y *= scale; qf[j].z *= scale; qf[j].w *= scale;
+        }
+    }
+    f32x16 o[DH / 32];
+#pragma unroll
+    for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[j][v] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+    const int pos_q = P + t_q;
+    // diagonal of this wave's tile; a tile that starts past the last row has nothing to do
+    const int last_key = qg * 128 + wq * 32 < a.T ? P + min(qg * 128 + wq * 32 + 31, a.T - 1) : -1;
+
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s) issue(s);
+    for (int step = 0; step < steps; ++step) {
+        wait_vmcnt<NPER*(STAGES - 2)>();
+        __syncthreads();
+        issue(step + STAGES - 1);
+        const int k0 = (step * KS + g) * 32;
+        if (k0 > last_key) continue;              // above this wave's diagonal (it still fetched and synchronised)
+        const char* sK = ring + (g * STAGES + step % STAGES) * STAGE_B;
+        const char* sV = sK + TILE_B;
+        f32x16 s;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[v] = 0.f;
+        if constexpr (F16) {
+#pragma unroll
+            for (int j = 0; j < DH / 16; ++j) {
+                const float4 kf = *reinterpret_cast<const float4*>(sK + l32 * ROWB + (((j * 2 + half) ^ swz_k(l32)) << 4));
+                s = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, kf), __builtin_bit_cast(f16x8_t, qf[j]), s, 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < DH / 8; ++j) {
+                const float4 kf = *reinterpret_cast<const float4*>(sK + l32 * ROWB + (((j * 2 + half) ^ swz_k(l32)) << 4));
+                s = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.x, qf[j].x, s, 0, 0, 0);
+                s = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.y, qf[j].y, s, 0, 0, 0);
+                s = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.z, qf[j].z, s, 0, 0, 0);
+                s = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.w, qf[j].w, s, 0, 0, 0);
+            }
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int key = k0 + (v >> 2) * 8 + half * 4 + (v & 3);
+            if (key > pos_q) s[v] = -INFINITY;
+            mx = fmaxf(mx, s[v]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float corr = __expf(m_run - m_use);
+        float rs = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            s[v] = __expf(s[v] - m_use);
+            rs += s[v];
+        }
+        rs += __shfl_xor(rs, 32, 64);
+        l_run = l_run * corr + rs;
+        m_run = m_new;
+#pragma unroll
+        for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[j][v] *= corr;
+        // O^T += V^T P^T; register v of a lane is key (v/4)*8 + 4*half + v%4 of the block
+        if constexpr (F16) {
+#pragma unroll
+            for (int mm = 0; mm < 2; ++mm) {
+                f16x8_t pf;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) pf[i] = static_cast<f16_t>(s[mm * 8 + i]);
+#pragma unroll
+                for (int j = 0; j < DH / 32; ++j) {
+                    f16x8_t vf;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const int r = mm * 16 + (i >> 2) * 8 + half * 4 + (i & 3);
+                        const int d = j * 32 + l32;
+                        vf[i] = *reinterpret_cast<const f16_t*>(sV + r * ROWB + (((d >> 3) ^ swz_v(r)) << 4) + (d & 7) * 2);
+                    }
+                    o[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf, o[j], 0, 0, 0);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int r = (v >> 2) * 8 + half * 4 + (v & 3);
+#pragma unroll
+                for (int j = 0; j < DH / 32; ++j) {
+                    const int d = j * 32 + l32;
+                    const float vv = *reinterpret_cast<const float*>(sV + r * ROWB + (((d >> 2) ^ swz_v(r)) << 4) + (d & 3) * 4);
+                    o[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(vv, s[v], o[j], 0, 0, 0);
+                }
+            }
+        }
+    }
+    wait_vmcnt<0>();
+
+    // merge the key-split groups in group order (group 0 holds the result)
+    if constexpr (KS > 1) {
+        __syncthreads();                          // every wave is done with the ring
+        float* xo = reinterpret_cast<float*>(ring);                    // [QT][DH/32*16][64]
+        float* xm = xo + QT * (DH / 32 * 16) * 64;                     // [QT][2][64]
+        for (int src = 1; src < KS; ++src) {
+            if (g == src) {
+#pragma unroll
+                for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) xo[(wq * (DH / 32 * 16) + j * 16 + v) * 64 + lane] = o[j][v];
+                xm[(wq * 2 + 0) * 64 + lane] = m_run;
+                xm[(wq * 2 + 1) * 64 + lane] = l_run;
+            }
+            __syncthreads();
+            if (g == 0) {
+                const float m2 = xm[(wq * 2 + 0) * 64 + lane], l2 = xm[(wq * 2 + 1) * 64 + lane];
+                const float m_new = fmaxf(m_run, m2);
+                const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+                const float c1 = __expf(m_run - m_use), c2 = __expf(m2 - m_use);
+                l_run = l_run * c1 + l2 * c2;
+                m_run = m_new;
+#pragma unroll
+                for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        o[j][v] = o[j][v] * c1 + xo[(wq * (DH / 32 * 16) + j * 16 + v) * 64 + lane] * c2;
+            }
+            __syncthreads();
+        }
+    }
+    if (g != 0 || t_q >= a.T) return;
+    const float inv = 1.0f / l_run;
+    typedef typename ActOf<KT>::type OT;
+    OT* op = static_cast<OT*>(a.o) + (static_cast<size_t>(b) * a.T + t_q) * a.hq * DH + h * DH;
+#pragma unroll
+    for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+            const int d = j * 32 + vq * 8 + half * 4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) op[d + i] = Elem<OT>::from_f32(o[j][vq * 4 + i] * inv);
+        }
+}
+
+template <typename KT, int DH, int KS, int STAGES>
+static void launch_pa_lds(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st) {
+    constexpr size_t lds = 2048 * 4 + static_cast<size_t>(KS) * STAGES * 2 * 32 * DH * sizeof(KT);
+    static_assert(lds <= 160 * 1024, "LDS of a compute unit");
+    static_assert(KS == 1 || static_cast<size_t>(KS) * STAGES * 2 * 32 * DH * sizeof(KT) >= 4 * (DH / 32 * 16 + 2) * 64 * 4,
+                  "the merge buffer lives in the ring");
+    static bool prepared = false;
+    if (!prepared) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_attn_lds_kernel<KT, DH, KS, STAGES>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        prepared = true;
+    }
+    const dim3 grid((a.T + 127) / 128, a.hq, a.B);
+    launch(prefill_attn_lds_kernel<KT, DH, KS, STAGES>, grid, dim3(256 * KS), lds, st, a, sb);
+}
+
 void launch_prefill_attn(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st) {
+    // LDS-staged kernel for the usual head sizes (activations and cache of one type), as long
+    // as every sequence's block-table row fits the kernel's LDS copy
+    int max_ctx = 0;
+    for (int b = 0; b < sb.n; ++b) max_ctx = max_ctx > sb.pos[b] + a.T ? max_ctx : sb.pos[b] + a.T;
+    const bool fits = (max_ctx - 1) / a.kv.page + 1 <= 2048;
+    if (!fits) {
+    } else if (a.kv_dtype == DT_F32 && a.out_dtype == DT_F32) {
+        if (a.kv.dh == 128) return launch_pa_lds<float, 128, 2, 2>(a, sb, st);
+        if (a.kv.dh == 64) return launch_pa_lds<float, 64, 2, 3>(a, sb, st);
+    }
+    else if (a.kv_dtype != DT_F32 && a.out_dtype != DT_F32) {
+        if (a.kv.dh == 128) return launch_pa_lds<f16_t, 128, 2, 3>(a, sb, st);
+        if (a.kv.dh == 64) return launch_pa_lds<f16_t, 64, 2, 3>(a, sb, st);
+    }
     if (a.kv_dtype == DT_F32) {
         if (a.out_dtype == DT_F32) launch_pa<float, float>(a, sb, st);
         else launch_pa<float, f16_t>(a, sb, st);
