@@ -24,10 +24,17 @@ class PlanProblem(C.Structure):
                 ("mem_bytes", C.POINTER(C.c_double)), ("bandwidth", C.POINTER(C.c_double))]
 
 
+class PipelineProblem(C.Structure):
+    _fields_ = [("n_stages", C.c_int32), ("n_micro", C.c_int32), ("n_decode", C.c_int32),
+                ("t_prefill", C.POINTER(C.c_double)), ("t_decode", C.POINTER(C.c_double)),
+                ("c_prefill", C.POINTER(C.c_double)), ("c_decode", C.POINTER(C.c_double)),
+                ("c_return", C.c_double)]
+
+
 EXPORTS = (
     "shard_create", "shard_destroy", "shard_seq_alloc", "shard_seq_free", "shard_seq_len",
     "shard_prefill", "shard_decode", "shard_profile", "shard_timing_enable", "shard_timing_read",
-    "shard_last_error", "shard_plan_latency", "shard_plan_throughput",
+    "shard_last_error", "shard_plan_latency", "shard_plan_throughput", "shard_simulate_pipeline",
 )
 
 
@@ -88,6 +95,7 @@ def load():
     lib.shard_timing_read.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double)]
     lib.shard_plan_latency.argtypes = [C.POINTER(PlanProblem), C.POINTER(i32), C.POINTER(C.c_double)]
     lib.shard_plan_throughput.argtypes = [C.POINTER(PlanProblem), i32, C.POINTER(i32), C.POINTER(C.c_double)]
+    lib.shard_simulate_pipeline.argtypes = [C.POINTER(PipelineProblem), i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.shard_last_error.argtypes = []
     lib.shard_last_error.restype = C.c_char_p
     for name in EXPORTS:
@@ -245,3 +253,37 @@ def plan_throughput(prob: dict, with_return_hop: bool = False):
     if rc:
         raise ShardError(rc, "no feasible placement" if rc == -2 else "bad planner arguments")
     return t.value, list(dev)
+
+
+def simulate_pipeline(t_prefill, t_decode, c_prefill, c_decode, c_return, n_micro, n_decode, no_bubbles):
+    """shard_simulate_pipeline: returns (makespan in seconds, busy seconds per stage)."""
+    dbl = lambda a: np.ascontiguousarray(a, dtype=np.float64)
+    tp, td, cp, cd = dbl(t_prefill), dbl(t_decode), dbl(c_prefill), dbl(c_decode)
+    S = len(tp)
+    ptr = lambda a: a.ctypes.data_as(C.POINTER(C.c_double)) if len(a) else None
+    pp = PipelineProblem(S, n_micro, n_decode, ptr(tp), ptr(td), ptr(cp), ptr(cd), float(c_return))
+    span = C.c_double()
+    busy = (C.c_double * max(1, S))()
+    rc = load().shard_simulate_pipeline(C.byref(pp), 1 if no_bubbles else 0, C.byref(span), busy)
+    if rc:
+        raise ShardError(rc, "bad pipeline problem")
+    return span.value, list(busy)[:S]
+
+
+def stages_of_plan(device_of_layer, t_prefill_layer, t_decode_layer, act_bytes_prefill, act_bytes_decode, bandwidth):
+    """Collapse a throughput plan (one contiguous layer range per device) into the per-stage
+    times and link times shard_simulate_pipeline takes.  Per-layer times are [N][M] (layer,
+    device), activation sizes [N], bandwidth [M][M] in bytes per second."""
+    dev = list(device_of_layer)
+    stages = [d for i, d in enumerate(dev) if i == 0 or dev[i - 1] != d]
+    tp, td, cp, cd = [], [], [], []
+    for d in stages:
+        idx = [i for i, x in enumerate(dev) if x == d]
+        tp.append(float(sum(t_prefill_layer[i][d] for i in idx)))
+        td.append(float(sum(t_decode_layer[i][d] for i in idx)))
+    for a, b in zip(stages[:-1], stages[1:]):
+        last = max(i for i, x in enumerate(dev) if x == a)
+        cp.append(float(act_bytes_prefill[last]) / float(bandwidth[a][b]))
+        cd.append(float(act_bytes_decode[last]) / float(bandwidth[a][b]))
+    c_ret = 0.0 if stages[-1] == stages[0] else float(act_bytes_decode[len(dev) - 1]) / float(bandwidth[stages[-1]][stages[0]])
+    return dict(stages=stages, t_prefill=tp, t_decode=td, c_prefill=cp, c_decode=cd, c_return=c_ret)

@@ -8,7 +8,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libshard.so")
-SOURCES = ("shard.cpp", "planner.cpp", "decode_kernels.hip", "prefill_kernels.hip")
+SOURCES = ("shard.cpp", "planner.cpp", "schedule.cpp", "decode_kernels.hip", "prefill_kernels.hip")
 FLAGS = (
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
     # keep the compiler from forming packed-fp32 ALU ops

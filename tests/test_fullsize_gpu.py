@@ -101,6 +101,12 @@ def test_config4_llama2_13b_layers_0_19_bf16_eight_microbatches(lib):
     run_fullsize(lib, "c4", list(range(8)), batched=False)
 
 
+def test_config4_fused_into_one_batch_of_eight(lib):
+    """The same eight sequences carried by single calls (batch 8): a 2048-row prefill and
+    8-row decode steps.  Sequences are independent, so the stored oracle rows still apply."""
+    run_fullsize(lib, "c4", list(range(8)), batched=True)
+
+
 def test_config5_llama2_70b_layers_0_19_gqa_bf16_batch16(lib):
     """70B shape (64 query / 8 KV heads), 20 layers, bf16, batch 16, 512 + 128, 16-token
     pages.  The oracle ran sequences 0 and 15 (batch independence is one of its pins); the
