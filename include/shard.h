@@ -178,6 +178,42 @@ enum {
 int shard_timing_enable(shard_t *s, int32_t on);
 int shard_timing_read(shard_t *s, int64_t launches[SHARD_K_COUNT], double seconds[SHARD_K_COUNT]);
 
+/* ---- The ends of a model around its decoder layers -------------------------------------
+ * The paper counts "an embedding layer, multiple decoder layers and an output layer" among
+ * the N layers it places (Sec. 4 "System Model") and pins the first of them, which sees the
+ * raw input tokens, to the source node (Eq. 4).  A shard maps hidden states to hidden
+ * states; these entry points supply what comes before the first shard and after the last:
+ * the token embedding lookup, and the final RMSNorm + output projection ("LM head") with a
+ * greedy choice of the next token, so that a whole token loop can run on library calls.
+ * The vocabulary size is the model's (32000 for Llama 2; not stated in the paper).
+ * An ends object holds whichever of the two ends it was given; same conventions as above. */
+typedef struct shard_ends shard_ends_t;
+
+/* tok_embeddings [vocab, d_model] and lm_head [vocab, d_model] are row-major in
+ * model->weight_dtype (bf16 as raw 16-bit patterns, converted once to IEEE half like the
+ * layer matrices); g_final is float32 [d_model].  tok_embeddings may be NULL (no embedding
+ * end), and so may g_final together with lm_head (no output end); at least one end must be
+ * given.  Copies everything; blocks until the upload is complete.  max_tokens >= 1 is the
+ * largest n of one shard_ends_embed call. */
+int shard_ends_create(shard_ends_t **out, const shard_model_cfg *model, int32_t vocab, int32_t max_tokens,
+                      const void *tok_embeddings, const float *g_final, const void *lm_head,
+                      int32_t weights_on_device);
+int shard_ends_destroy(shard_ends_t *e);
+
+/* x_out[i, :] = tok_embeddings[token_ids[i], :] as float32, i < n.  token_ids: HOST pointer
+ * (the ids are validated here: an id outside [0, vocab) is SHARD_E_INVAL and nothing is
+ * enqueued).  x_out: device pointer, float32 [n, d_model]. */
+int shard_ends_embed(shard_ends_t *e, const int32_t *token_ids, int32_t n, void *x_out, void *hip_stream);
+
+/* logits[i, :] = lm_head . rmsnorm(x[i, :]; g_final), i < n, 1 <= n <= SHARD_MAX_BATCH.
+ * x: device float32 [n, d_model] (the last shard's output for the tokens whose successor is
+ * wanted); logits: device float32 [n, vocab]. */
+int shard_ends_logits(shard_ends_t *e, const void *x, int32_t n, void *logits, void *hip_stream);
+
+/* token_ids_out[i] = argmax_j logits[i, j] (greedy decoding; the lowest index among equal
+ * maxima).  logits: device float32 [n, vocab]; token_ids_out: device int32 [n]. */
+int shard_ends_argmax(shard_ends_t *e, const void *logits, int32_t n, int32_t *token_ids_out, void *hip_stream);
+
 /* Message for the most recent failure on this thread ("" if none). */
 const char *shard_last_error(void);
 

@@ -31,6 +31,8 @@ float32 arrays (exactly representing fp32 or bf16 values) and are widened, never
 Library routine used as a step: numpy's float64 matmul.  No tiling, fusion or paging: the
 cache is a plain [position, kv_head, dh] array per layer and sequence.
 
+The ends of a model (embed, logits, greedy) are at the bottom of the file.
+
 Parity status of this file: every function is pinned by tests/test_oracle_pins.py
 (pure-Python brute force on tiny shapes, closed forms, invariants, independent library
 routines).  Unpinned: agreement of the RoPE pairing convention with real Llama 2
@@ -157,6 +159,26 @@ class OracleShard:
         h2 = rmsnorm(x1, w["g_ffn"], self.eps)
         f = silu(h2 @ wide("w_gate").T) * (h2 @ wide("w_up").T)
         return x1 + f @ wide("w_down").T
+
+
+# ---- the ends of a model around its decoder layers (the "embedding layer" and "output layer"
+# the paper counts among the N layers, Sec. 4 "System Model"; the first is pinned to the
+# source node by Eq. 4).  Plain definitions of the Llama 2 ends: a table lookup, and the final
+# RMSNorm followed by the output projection; greedy decoding takes the largest logit.
+def embed(table: np.ndarray, token_ids) -> np.ndarray:
+    """x[i, :] = table[token_ids[i], :] in float64."""
+    return np.stack([np.asarray(table[int(t)], dtype=np.float64) for t in token_ids])
+
+
+def logits(x: np.ndarray, g_final: np.ndarray, lm_head: np.ndarray, eps: float) -> np.ndarray:
+    """logits[i, v] = sum_j lm_head[v, j] * rmsnorm(x[i]; g_final)[j], float64."""
+    h = rmsnorm(np.asarray(x, dtype=np.float64), np.asarray(g_final, dtype=np.float64), eps)
+    return h @ np.asarray(lm_head, dtype=np.float64).T
+
+
+def greedy(lg: np.ndarray) -> np.ndarray:
+    """Index of the largest logit of each row (the lowest index among equals)."""
+    return np.array([int(np.argmax(row)) for row in lg], dtype=np.int64)
 
 
 def params_per_layer(cfg: dict) -> int:

@@ -35,6 +35,7 @@ EXPORTS = (
     "shard_create", "shard_destroy", "shard_seq_alloc", "shard_seq_free", "shard_seq_len",
     "shard_prefill", "shard_decode", "shard_profile", "shard_timing_enable", "shard_timing_read",
     "shard_last_error", "shard_plan_latency", "shard_plan_throughput", "shard_simulate_pipeline",
+    "shard_ends_create", "shard_ends_destroy", "shard_ends_embed", "shard_ends_logits", "shard_ends_argmax",
 )
 
 
@@ -96,6 +97,11 @@ def load():
     lib.shard_plan_latency.argtypes = [C.POINTER(PlanProblem), C.POINTER(i32), C.POINTER(C.c_double)]
     lib.shard_plan_throughput.argtypes = [C.POINTER(PlanProblem), i32, C.POINTER(i32), C.POINTER(C.c_double)]
     lib.shard_simulate_pipeline.argtypes = [C.POINTER(PipelineProblem), i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.shard_ends_create.argtypes = [C.POINTER(vp), C.POINTER(ModelCfg), i32, i32, vp, vp, vp, i32]
+    lib.shard_ends_destroy.argtypes = [vp]
+    lib.shard_ends_embed.argtypes = [vp, C.POINTER(i32), i32, vp, vp]
+    lib.shard_ends_logits.argtypes = [vp, vp, i32, vp, vp]
+    lib.shard_ends_argmax.argtypes = [vp, vp, i32, vp, vp]
     lib.shard_last_error.argtypes = []
     lib.shard_last_error.restype = C.c_char_p
     for name in EXPORTS:
@@ -208,6 +214,41 @@ class Shard:
         s = (C.c_double * K_COUNT)()
         _check(load().shard_timing_read(self._h, n, s))
         return {KERNEL_CLASSES[k]: {"launches": n[k], "seconds": s[k]} for k in range(K_COUNT)}
+
+
+class ShardEnds:
+    """Embedding table and/or final norm + LM head on the current device (host numpy arrays:
+    float32 for SHARD_F32, uint16 bf16 bit patterns for SHARD_BF16; g_final float32)."""
+
+    def __init__(self, cfg: dict, vocab: int, *, tok_embeddings=None, g_final=None, lm_head=None,
+                 weight_dtype: int = SHARD_F32, max_tokens: int = 4096):
+        self._h = C.c_void_p()
+        self.vocab = vocab
+        mc = model_cfg(cfg, weight_dtype)
+        keep = [None if t is None else np.ascontiguousarray(t) for t in (tok_embeddings, g_final, lm_head)]
+        _check(load().shard_ends_create(C.byref(self._h), C.byref(mc), vocab, max_tokens,
+                                        _ptr(keep[0]), _ptr(keep[1]), _ptr(keep[2]), 0))
+
+    def close(self):
+        if self._h:
+            _check(load().shard_ends_destroy(self._h))
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def embed(self, token_ids, x_out, stream: int = 0) -> None:
+        ids, n = _ids(token_ids)
+        _check(load().shard_ends_embed(self._h, ids, n, _ptr(x_out), stream))
+
+    def logits(self, x, n: int, logits_out, stream: int = 0) -> None:
+        _check(load().shard_ends_logits(self._h, _ptr(x), n, _ptr(logits_out), stream))
+
+    def argmax(self, logits, n: int, ids_out, stream: int = 0) -> None:
+        _check(load().shard_ends_argmax(self._h, _ptr(logits), n, _ptr(ids_out), stream))
 
 
 def pack_layers(layers: list, weight_dtype: int) -> list:

@@ -122,12 +122,12 @@ __global__ __launch_bounds__(256) void decode_linear_kernel(DecodeLinear a, SeqB
     }
     __syncthreads();
 
-    if (a.epi == EPI_RESID) {
+    if (a.epi == EPI_RESID || a.epi == EPI_STORE) {
         if (tid < R * NB) {
             const int r = tid / NB, b = tid % NB, n = row0 + r;
             if (n < a.N && b < a.nb) {
                 const size_t i = static_cast<size_t>(b) * a.N + n;
-                a.out[i] = a.resid[i] + s_val[tid];
+                a.out[i] = a.epi == EPI_RESID ? a.resid[i] + s_val[tid] : s_val[tid];
             }
         }
         return;
@@ -547,6 +547,74 @@ __global__ void table_update_kernel(int32_t* table, TableUpdate u) {
 
 void launch_table_update(int32_t* table, const TableUpdate& u, hipStream_t st) {
     launch(table_update_kernel, dim3(1), dim3(128), 0, st, table, u);
+}
+
+// ---------------------------------------------------------------------------------------
+// The ends of a model around its decoder layers: token embedding lookup and greedy choice.
+// ---------------------------------------------------------------------------------------
+template <typename WT>
+__global__ __launch_bounds__(256) void embed_kernel(const WT* __restrict__ table, int V, int d, TokenIds by_value,
+                                                    const int32_t* __restrict__ ids_dev, float* __restrict__ x_out,
+                                                    uint32_t* bad) {
+    constexpr int VEC = Elem<WT>::VEC;
+    const int i = blockIdx.x;
+    int id = ids_dev ? ids_dev[i] : by_value.id[i];
+    if (id < 0 || id >= V) {
+        if (threadIdx.x == 0) atomicOr(bad, 1u);
+        id = id < 0 ? 0 : V - 1;
+    }
+    const WT* row = table + static_cast<size_t>(id) * d;
+    float* out = x_out + static_cast<size_t>(i) * d;
+    for (int c = threadIdx.x; c < d / VEC; c += 256) {
+        Vec16<WT> w;
+        w.load(row + static_cast<size_t>(c) * VEC);
+#pragma unroll
+        for (int e = 0; e < VEC; e += 4) {
+            float4 o;
+            o.x = w.v[e]; o.y = w.v[e + 1]; o.z = w.v[e + 2]; o.w = w.v[e + 3];
+            *reinterpret_cast<float4*>(out + static_cast<size_t>(c) * VEC + e) = o;
+        }
+    }
+}
+
+void launch_embed(const void* table, int32_t dt, int32_t V, int32_t d, const TokenIds* by_value, const int32_t* ids_dev,
+                  int32_t n, float* x_out, uint32_t* bad, hipStream_t st) {
+    TokenIds none{};
+    const TokenIds& ids = by_value ? *by_value : none;
+    if (dt == DT_F32)
+        launch(embed_kernel<float>, dim3(n), dim3(256), 0, st, static_cast<const float*>(table), V, d, ids, ids_dev, x_out, bad);
+    else
+        launch(embed_kernel<f16_t>, dim3(n), dim3(256), 0, st, static_cast<const f16_t*>(table), V, d, ids, ids_dev, x_out, bad);
+}
+
+__global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ logits, int V, int32_t* __restrict__ out) {
+    const float* row = logits + static_cast<size_t>(blockIdx.x) * V;
+    float best = -INFINITY;
+    int at = 0x7fffffff;
+    for (int i = threadIdx.x; i < V; i += 256) {
+        const float v = row[i];
+        if (v > best || (v == best && i < at)) { best = v; at = i; }   // NaN compares false: skipped
+    }
+    // lowest index among equal maxima, in every reduction step
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const float ob = __shfl_xor(best, off, 64);
+        const int oa = __shfl_xor(at, off, 64);
+        if (ob > best || (ob == best && oa < at)) { best = ob; at = oa; }
+    }
+    __shared__ float s_b[4];
+    __shared__ int s_a[4];
+    if ((threadIdx.x & 63) == 0) { s_b[threadIdx.x >> 6] = best; s_a[threadIdx.x >> 6] = at; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w)
+            if (s_b[w] > best || (s_b[w] == best && s_a[w] < at)) { best = s_b[w]; at = s_a[w]; }
+        out[blockIdx.x] = at == 0x7fffffff ? 0 : at;
+    }
+}
+
+void launch_argmax(const float* logits, int32_t n, int32_t V, int32_t* out, hipStream_t st) {
+    launch(argmax_kernel, dim3(n), dim3(256), 0, st, logits, V, out);
 }
 
 }  // namespace shk

@@ -66,7 +66,8 @@ __device__ __forceinline__ size_t kv_row(const KvView& kv, const int32_t* bt, in
 enum Epilogue {
     EPI_QKV = 0,     // RoPE on q,k; q -> q buffer (fp32); k,v -> cache pages
     EPI_RESID = 1,   // out = resid + acc   (fp32)
-    EPI_SWIGLU = 2   // rows (2f, 2f+1) = (gate_f, up_f): out[f] = silu(gate) * up
+    EPI_SWIGLU = 2,  // rows (2f, 2f+1) = (gate_f, up_f): out[f] = silu(gate) * up
+    EPI_STORE = 3    // out = acc   (fp32; decode path only: the LM head)
 };
 
 // y = W x for a few activation rows (decode): W [N, K] row-major (dtype wt), x fp32 [nb, K].
@@ -156,5 +157,18 @@ struct TableUpdate {
     int32_t val[128];
 };
 void launch_table_update(int32_t* table, const TableUpdate& u, hipStream_t st);
+
+// x_out[i, :] = table[ids[i], :] widened to fp32 (table [V, d] in dtype dt).  Ids come either
+// by value (n <= 128) or from device memory; an id outside [0, V) is clamped and *bad is set.
+struct TokenIds {
+    int32_t n;
+    int32_t id[128];
+};
+void launch_embed(const void* table, int32_t dt, int32_t V, int32_t d, const TokenIds* by_value, const int32_t* ids_dev,
+                  int32_t n, float* x_out, uint32_t* bad, hipStream_t st);
+
+// out[i] = index of the largest of logits[i, 0..V) (the lowest index among equals; NaNs are
+// never chosen unless the whole row is NaN, which gives 0).
+void launch_argmax(const float* logits, int32_t n, int32_t V, int32_t* out, hipStream_t st);
 
 }  // namespace shk

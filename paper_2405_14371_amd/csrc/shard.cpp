@@ -87,6 +87,7 @@ struct shard {
     float* part_ml = nullptr;
     int nsplit_max = 32;
     Timing timing;
+    uint32_t* cvt_flag = nullptr;   // overflow flag of the bf16 -> half conversion during create
     std::vector<hipEvent_t> layer_ev;  // L+1 events, used by shard_profile
     bool record_layers = false;
 };
@@ -99,7 +100,7 @@ void free_all(shard* s) {
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
     }
-    void* ptrs[] = {s->rope, s->block_table, s->h, s->q, s->o, s->f, s->part_o, s->part_ml};
+    void* ptrs[] = {s->rope, s->block_table, s->h, s->q, s->o, s->f, s->part_o, s->part_ml, s->cvt_flag};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     for (auto& v : s->timing.ev)
@@ -455,7 +456,7 @@ int shard_create(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg
     } while (0)
 
     const size_t page_elems = static_cast<size_t>(model->n_kv_heads) * kv->page_size * dh;
-    uint32_t* cvt_flag = nullptr;
+    uint32_t*& cvt_flag = s->cvt_flag;  // owned by the shard, so every failure path releases it
     for (int i = 0; i < L; ++i) {
         LayerDev& l = s->layers[i];
         CREATE_TRY(hipMalloc(&l.wqkv, static_cast<size_t>(s->nqkv) * d * es));
@@ -532,6 +533,7 @@ int shard_create(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg
         uint32_t over = 0;
         const hipError_t e1 = hipMemcpy(&over, cvt_flag, sizeof over, hipMemcpyDeviceToHost);
         (void)hipFree(cvt_flag);
+        cvt_flag = nullptr;
         if (e1 != hipSuccess || over) {
             free_all(s);
             return e1 != hipSuccess ? fail(SHARD_E_HIP, "reading the conversion flag: %s", hipGetErrorString(e1))
@@ -706,6 +708,143 @@ int shard_profile(shard_t* s, int32_t B, int32_t T_prefill, int32_t n_decode, in
         p.kv_bytes_per_token = 2ull * m.n_kv_heads * m.head_dim * s->es;
     }
     return SHARD_OK;
+}
+
+// ---- the ends of a model: embedding lookup, final norm + LM head, greedy choice ----------
+}  // extern "C"
+
+struct shard_ends {
+    shard_model_cfg m{};
+    int vocab = 0, max_tokens = 0, dt = DT_F32;
+    size_t es = 4;
+    void* tok = nullptr;       // [V, d]
+    void* lm = nullptr;        // [V, d]
+    float* g_final = nullptr;  // [d]
+    int32_t* ids_dev = nullptr;
+    uint32_t* flag = nullptr;  // conversion overflow / clamped-id flag
+};
+
+namespace {
+void free_ends(shard_ends* e) {
+    void* ptrs[] = {e->tok, e->lm, e->g_final, e->ids_dev, e->flag};
+    for (void* p : ptrs)
+        if (p) (void)hipFree(p);
+    delete e;
+}
+}  // namespace
+
+extern "C" {
+
+int shard_ends_create(shard_ends_t** out, const shard_model_cfg* model, int32_t vocab, int32_t max_tokens,
+                      const void* tok_embeddings, const float* g_final, const void* lm_head, int32_t weights_on_device) {
+    if (!out) return fail(SHARD_E_INVAL, "null out");
+    *out = nullptr;
+    if (!model) return fail(SHARD_E_INVAL, "null model");
+    if (model->d_model < 8 || model->d_model % 8) return fail(SHARD_E_INVAL, "d_model must be a positive multiple of 8");
+    if (model->weight_dtype != SHARD_F32 && model->weight_dtype != SHARD_BF16)
+        return fail(SHARD_E_INVAL, "unknown weight_dtype %d", model->weight_dtype);
+    if (!(model->rms_eps >= 0.f)) return fail(SHARD_E_INVAL, "bad rms_eps");
+    if (vocab < 1 || max_tokens < 1) return fail(SHARD_E_INVAL, "vocab and max_tokens must be positive");
+    if (!tok_embeddings && !lm_head) return fail(SHARD_E_INVAL, "neither end given");
+    if ((g_final == nullptr) != (lm_head == nullptr)) return fail(SHARD_E_INVAL, "g_final and lm_head go together");
+    shard_ends* e = new (std::nothrow) shard_ends();
+    if (!e) return fail(SHARD_E_NOMEM, "host allocation failed");
+    e->m = *model;
+    e->vocab = vocab;
+    e->max_tokens = max_tokens;
+    e->es = model->weight_dtype == SHARD_F32 ? 4 : 2;
+    e->dt = model->weight_dtype == SHARD_F32 ? DT_F32 : DT_F16;
+    const size_t elems = static_cast<size_t>(vocab) * model->d_model;
+    const hipMemcpyKind kind = weights_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+#define ENDS_TRY(expr)                                                                        \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess) {                                                               \
+            free_ends(e);                                                                     \
+            return fail(e_ == hipErrorOutOfMemory ? SHARD_E_NOMEM : SHARD_E_HIP, "%s: %s", #expr, \
+                        hipGetErrorString(e_));                                               \
+        }                                                                                     \
+    } while (0)
+    ENDS_TRY(hipMalloc(reinterpret_cast<void**>(&e->flag), sizeof(uint32_t)));
+    ENDS_TRY(hipMemset(e->flag, 0, sizeof(uint32_t)));
+    if (tok_embeddings) {
+        ENDS_TRY(hipMalloc(&e->tok, elems * e->es));
+        ENDS_TRY(hipMemcpy(e->tok, tok_embeddings, elems * e->es, kind));
+        ENDS_TRY(hipMalloc(reinterpret_cast<void**>(&e->ids_dev), static_cast<size_t>(max_tokens) * sizeof(int32_t)));
+        if (model->weight_dtype == SHARD_BF16) launch_bf16_to_f16(e->tok, elems, e->flag, nullptr);
+    }
+    if (lm_head) {
+        ENDS_TRY(hipMalloc(&e->lm, elems * e->es));
+        ENDS_TRY(hipMemcpy(e->lm, lm_head, elems * e->es, kind));
+        ENDS_TRY(hipMalloc(reinterpret_cast<void**>(&e->g_final), model->d_model * sizeof(float)));
+        ENDS_TRY(hipMemcpy(e->g_final, g_final, model->d_model * sizeof(float), kind));
+        if (model->weight_dtype == SHARD_BF16) launch_bf16_to_f16(e->lm, elems, e->flag, nullptr);
+    }
+    ENDS_TRY(hipDeviceSynchronize());
+    uint32_t over = 0;
+    ENDS_TRY(hipMemcpy(&over, e->flag, sizeof over, hipMemcpyDeviceToHost));
+#undef ENDS_TRY
+    if (over) {
+        free_ends(e);
+        return fail(SHARD_E_INVAL, "a bf16 weight exceeds the range of IEEE half (65504)");
+    }
+    *out = e;
+    return SHARD_OK;
+}
+
+int shard_ends_destroy(shard_ends_t* e) {
+    if (!e) return SHARD_OK;
+    const hipError_t rc = hipDeviceSynchronize();
+    free_ends(e);
+    if (rc != hipSuccess) return fail(SHARD_E_HIP, "hipDeviceSynchronize: %s", hipGetErrorString(rc));
+    return SHARD_OK;
+}
+
+int shard_ends_embed(shard_ends_t* e, const int32_t* token_ids, int32_t n, void* x_out, void* hip_stream) {
+    if (!e || !token_ids || !x_out) return fail(SHARD_E_INVAL, "null argument");
+    if (!e->tok) return fail(SHARD_E_STATE, "this ends object holds no embedding table");
+    if (n < 1 || n > e->max_tokens) return fail(SHARD_E_INVAL, "n = %d outside 1..max_tokens (%d)", n, e->max_tokens);
+    for (int i = 0; i < n; ++i)
+        if (token_ids[i] < 0 || token_ids[i] >= e->vocab)
+            return fail(SHARD_E_INVAL, "token_ids[%d] = %d outside the vocabulary (%d)", i, token_ids[i], e->vocab);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (n <= 128) {
+        TokenIds ids{};
+        ids.n = n;
+        for (int i = 0; i < n; ++i) ids.id[i] = token_ids[i];
+        launch_embed(e->tok, e->dt, e->vocab, e->m.d_model, &ids, nullptr, n, static_cast<float*>(x_out), e->flag, st);
+    } else {
+        // the copy from pageable host memory completes (from the host's view) before this returns
+        HIP_TRY(hipMemcpyAsync(e->ids_dev, token_ids, static_cast<size_t>(n) * sizeof(int32_t), hipMemcpyHostToDevice, st));
+        launch_embed(e->tok, e->dt, e->vocab, e->m.d_model, nullptr, e->ids_dev, n, static_cast<float*>(x_out), e->flag, st);
+    }
+    return check_launch();
+}
+
+int shard_ends_logits(shard_ends_t* e, const void* x, int32_t n, void* logits, void* hip_stream) {
+    if (!e || !x || !logits) return fail(SHARD_E_INVAL, "null argument");
+    if (!e->lm) return fail(SHARD_E_STATE, "this ends object holds no output projection");
+    if (n < 1 || n > SHARD_MAX_BATCH) return fail(SHARD_E_INVAL, "n = %d outside 1..%d", n, SHARD_MAX_BATCH);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    SeqBatch sb{};
+    for (int r0 = 0; r0 < n; r0 += 8) {  // the streaming projection takes up to 8 rows per pass
+        DecodeLinear d{};
+        d.W = e->lm; d.N = e->vocab; d.K = e->m.d_model; d.wt = e->dt;
+        d.nb = n - r0 < 8 ? n - r0 : 8;
+        d.x = static_cast<const float*>(x) + static_cast<size_t>(r0) * e->m.d_model;
+        d.gain = e->g_final; d.eps = e->m.rms_eps; d.epi = EPI_STORE;
+        d.out = static_cast<float*>(logits) + static_cast<size_t>(r0) * e->vocab;
+        sb.n = d.nb;
+        launch_decode_linear(d, sb, st);
+    }
+    return check_launch();
+}
+
+int shard_ends_argmax(shard_ends_t* e, const void* logits, int32_t n, int32_t* token_ids_out, void* hip_stream) {
+    if (!e || !logits || !token_ids_out) return fail(SHARD_E_INVAL, "null argument");
+    if (n < 1) return fail(SHARD_E_INVAL, "n must be positive");
+    launch_argmax(static_cast<const float*>(logits), n, e->vocab, token_ids_out, static_cast<hipStream_t>(hip_stream));
+    return check_launch();
 }
 
 }  // extern "C"

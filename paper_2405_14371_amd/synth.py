@@ -94,6 +94,21 @@ def shard_weights(cfg: dict, seed: int, layer_lo: int, layer_hi: int, dtype: str
     return [layer_weights(cfg, seed, layer, dtype) for layer in range(layer_lo, layer_hi)]
 
 
+def ends_weights(cfg: dict, seed: int, vocab: int, dtype: str = "f32") -> dict:
+    """Token embedding table and LM head [vocab, d_model] (N(0, 0.02^2), bf16-rounded if
+    dtype='bf16') and a non-trivial final norm gain, as float32 arrays."""
+    if dtype not in ("f32", "bf16"):
+        raise ValueError(dtype)
+    out = {}
+    for idx, name in enumerate(("tok_embeddings", "lm_head")):
+        w = _stream(seed, 4, idx).standard_normal((vocab, cfg["d_model"]), dtype=np.float32)
+        w *= np.float32(WEIGHT_STD)
+        out[name] = round_to_bf16(w) if dtype == "bf16" else w
+    g = _stream(seed, 4, 2).standard_normal(cfg["d_model"], dtype=np.float32)
+    out["g_final"] = np.float32(1.0) + np.float32(0.1) * g
+    return out
+
+
 def random_gains(cfg: dict, seed: int, layer: int) -> dict:
     """Non-trivial norm gains (1 + 0.1 N(0,1)) for tests that must see the gain multiply."""
     g = _stream(seed, 3, layer).standard_normal((2, cfg["d_model"]), dtype=np.float32)

@@ -408,3 +408,30 @@ def test_planted_mistakes_are_caught(monkeypatch):
             got = run_oracle(cfg, layers, chunks)
             assert np.max(np.abs(got - want)) > 1e-6, f"pin blind to {mut.__name__}"
             monkeypatch.setattr(orc, name, original)
+
+
+# ---- the ends of a model (embedding, final norm + LM head, greedy choice) -------------------
+def test_ends_embedding_is_a_one_hot_product_and_logits_match_torch_f64():
+    import torch
+    rng = np.random.default_rng(11)
+    V, d = 37, 16
+    table = rng.standard_normal((V, d)).astype(np.float32)
+    ids = [0, 36, 5, 5, 20]
+    onehot = np.zeros((len(ids), V)); onehot[np.arange(len(ids)), ids] = 1.0
+    np.testing.assert_array_equal(orc.embed(table, ids), onehot @ table.astype(np.float64))
+    x = rng.standard_normal((4, d)); g = 1.0 + 0.1 * rng.standard_normal(d); W = rng.standard_normal((V, d))
+    want = torch.nn.functional.linear(
+        torch.nn.functional.rms_norm(torch.from_numpy(x), (d,), torch.from_numpy(g), 1e-5), torch.from_numpy(W)).numpy()
+    np.testing.assert_allclose(orc.logits(x, g, W, 1e-5), want, rtol=1e-12, atol=1e-12)
+
+
+def test_ends_logits_closed_form_and_greedy_rule():
+    d, V = 8, 5
+    W = np.arange(V * d, dtype=np.float64).reshape(V, d)
+    # a constant row c normalises to c / sqrt(c^2 + eps) in every element: logits are row sums times that
+    c, eps = 3.0, 0.25
+    lg = orc.logits(np.full((1, d), c), np.ones(d), W, eps)
+    np.testing.assert_allclose(lg[0], W.sum(axis=1) * c / np.sqrt(c * c + eps), rtol=1e-14)
+    # the gain multiplies after normalisation: doubling it doubles the logits
+    np.testing.assert_allclose(orc.logits(np.full((1, d), c), 2 * np.ones(d), W, eps), 2 * lg, rtol=1e-14)
+    assert list(orc.greedy(np.array([[1.0, 7.0, 7.0, 2.0], [-1.0, -3.0, -1.0, -5.0]]))) == [1, 0]
