@@ -178,10 +178,10 @@ def main():
     kt = sh.timing_read()
     sh.timing_enable(False)
     proj = ("qkv", "o", "gateup", "down")
-    # passes over a projection's weights: one per layer call, except that batches the decode
-    # kernels cannot take at once (fp32 > 8 rows, half > 16) go in chunks of 8 rows
-    one_pass = B <= 8 or (wl["dtype"] != "f32" and B <= 16)
-    calls_dec = L * n_dec * MB * (1 if one_pass else -(-B // 8))
+    # passes over a projection's weights: one per layer call and group of sequences the decode
+    # kernels take at once (fp32: 8 rows; half: 8 rows up to 4 sequences, else 16)
+    mfma_decode = wl["dtype"] != "f32" and B > 4
+    calls_dec = L * n_dec * MB * (-(-B // 16) if mfma_decode else -(-B // 8))
     calls_pre = L * MB
     lin = {f: sum(kt["decode_" + k][f] for k in proj) for f in ("launches", "seconds")}
     lin_bytes = sum(work["linear_bytes"].values()) * calls_dec
@@ -194,7 +194,6 @@ def main():
             traffic = json.load(fh)[args.workload]["decode_linear_kernel"]["traffic_bytes_per_launch"]
     except (OSError, KeyError, ValueError):
         pass
-    mfma_decode = wl["dtype"] != "f32" and 8 < B <= 16
     n_lin = 4 * calls_dec                   # projection launches (the batched path's RMSNorm launches not counted)
     roofline = {
         "kernel": ("decode_linear_mfma_kernel" if mfma_decode else "decode_linear_kernel")

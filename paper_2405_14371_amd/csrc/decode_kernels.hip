@@ -349,15 +349,16 @@ void launch_decode_linear_mfma(const DecodeLinear& a, const SeqBatch& sb, hipStr
 // ---------------------------------------------------------------------------------------
 constexpr int ATTN_MAX_SPLIT = 32;
 
-template <typename KT, int DH, int TU>
+template <typename KT, int DH, int TU, int GQ>
 __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttn a, SeqBatch sb) {
     constexpr int VEC = Elem<KT>::VEC;
     constexpr int TPT = DH / VEC;
     constexpr int GROUPS = 256 / TPT;
     const int tid = threadIdx.x;
-    const int split = blockIdx.x, bh = blockIdx.y;
-    const int b = bh / a.hq, h = bh % a.hq;
-    const int hk = h / (a.hq / a.kv.hkv);
+    const int split = blockIdx.x;
+    const int hgroups = a.hq / GQ;                 // GQ consecutive query heads (one KV head) per workgroup
+    const int b = blockIdx.y / hgroups, h0 = (blockIdx.y % hgroups) * GQ;
+    const int hk = h0 / (a.hq / a.kv.hkv);
     const int seq = sb.seq[b];
     const int ctx = sb.pos[b] + 1;  // the new token's k,v are already in the cache
     const int per = (ctx + a.nsplit - 1) / a.nsplit;
@@ -368,86 +369,144 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttn a, SeqBatch
     const KT* __restrict__ vp = static_cast<const KT*>(a.kv.v);
     const int32_t* bt = a.kv.block_table + static_cast<size_t>(seq) * a.kv.max_pages;
 
-    float qv[VEC];
-    {
-        const float* qp = a.q + static_cast<size_t>(b) * a.hq * DH + h * DH + e0;
+    float qv[GQ][VEC];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) qv[e] = qp[e] * scale;
+    for (int q = 0; q < GQ; ++q) {
+        const float* qp = a.q + static_cast<size_t>(b) * a.hq * DH + (h0 + q) * DH + e0;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) qv[q][e] = qp[e] * scale;
     }
-    float m = -INFINITY, l = 0.f, acc[VEC];
+    float m[GQ], l[GQ], acc[GQ][VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+    for (int q = 0; q < GQ; ++q) {
+        m[q] = -INFINITY;
+        l[q] = 0.f;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[q][e] = 0.f;
+    }
 
-    for (int u0 = u_begin + g; u0 < u_end; u0 += GROUPS * TU) {
-        Vec16<KT> kv[TU], vv[TU];
-        bool ok[TU];
+    // The slice's block-table entries go to LDS once, so that a trip's K/V addresses need no
+    // global load of their own; a slice with more pages than fit looks them up in memory.
+    constexpr int PG_CAP = 512;
+    __shared__ int32_t s_pg[PG_CAP];
+    const int pg_lo = u_begin < u_end ? u_begin / a.kv.page : 0;
+    const int pg_n = u_begin < u_end ? (u_end - 1) / a.kv.page - pg_lo + 1 : 0;
+    const bool pg_cached = pg_n <= PG_CAP;
+    if (pg_cached)
+        for (int i = tid; i < pg_n; i += 256) s_pg[i] = bt[pg_lo + i];
+    __syncthreads();
+
+    // One trip = TU tokens per lane group; the loads of trip t+1 are issued before trip t is
+    // worked on (the kernel is latency-bound: few trips, each a dependent chain of loads).
+    uint4 ka[TU], va[TU], kb[TU], vb[TU];          // two register sets, used alternately
+    auto fetch = [&](int u0, uint4 (&kr)[TU], uint4 (&vr)[TU]) {
 #pragma unroll
         for (int i = 0; i < TU; ++i) {
             const int u = u0 + i * GROUPS;
-            ok[i] = u < u_end;
-            const int uc = ok[i] ? u : u0;
-            const size_t at = kv_row_div(a.kv, bt, uc, hk) * DH + e0;
-            kv[i].load(kp + at);
-            vv[i].load(vp + at);
+            const int uc = u < u_end ? u : u_end - 1;
+            const int pg = uc / a.kv.page, slot = uc - pg * a.kv.page;
+            const int page_id = pg_cached ? s_pg[pg - pg_lo] : bt[pg];
+            const size_t at = ((static_cast<size_t>(page_id) * a.kv.hkv + hk) * a.kv.page + slot) * DH + e0;
+            kr[i] = *reinterpret_cast<const uint4*>(kp + at);
+            vr[i] = *reinterpret_cast<const uint4*>(vp + at);
         }
-        float s[TU], mn = m;
+    };
+    auto widen = [](const uint4& r, float* out) {
+        if constexpr (sizeof(KT) == 4) {
+            out[0] = __uint_as_float(r.x); out[1] = __uint_as_float(r.y);
+            out[2] = __uint_as_float(r.z); out[3] = __uint_as_float(r.w);
+        } else {
+            typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+            const h8 t = __builtin_bit_cast(h8, r);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) out[e] = static_cast<float>(t[e]);
+        }
+    };
+    auto work = [&](int u0, const uint4 (&kr)[TU], const uint4 (&vr)[TU]) {
+        float kf[TU][VEC], vf[TU][VEC];
+        bool ok[TU];
 #pragma unroll
         for (int i = 0; i < TU; ++i) {
-            float d = 0.f;
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) d = fmaf(qv[e], kv[i].v[e], d);
-#pragma unroll
-            for (int o = TPT / 2; o >= 1; o >>= 1) d += __shfl_xor(d, o, 64);
-            s[i] = ok[i] ? d : -INFINITY;
-            mn = fmaxf(mn, s[i]);
+            ok[i] = u0 + i * GROUPS < u_end;
+            widen(kr[i], kf[i]);
+            widen(vr[i], vf[i]);
         }
-        const float corr = __expf(m - mn);  // first trip: exp(-inf) = 0
-        l *= corr;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] *= corr;
+        for (int q = 0; q < GQ; ++q) {
+            float s[TU], mn = m[q];
 #pragma unroll
-        for (int i = 0; i < TU; ++i) {
-            const float p = __expf(s[i] - mn);
-            l += p;
+            for (int i = 0; i < TU; ++i) {
+                float d = 0.f;
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[e] = fmaf(p, vv[i].v[e], acc[e]);
+                for (int e = 0; e < VEC; ++e) d = fmaf(qv[q][e], kf[i][e], d);
+                d = group_sum<TPT>(d);
+                s[i] = ok[i] ? d : -INFINITY;
+                mn = fmaxf(mn, s[i]);
+            }
+            const float corr = __expf(m[q] - mn);  // first trip: exp(-inf) = 0
+            l[q] *= corr;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[q][e] *= corr;
+#pragma unroll
+            for (int i = 0; i < TU; ++i) {
+                const float p = __expf(s[i] - mn);
+                l[q] += p;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[q][e] = fmaf(p, vf[i][e], acc[q][e]);
+            }
+            m[q] = mn;
         }
-        m = mn;
+    };
+    constexpr int STEP = GROUPS * TU;
+    int u0 = u_begin + g;
+    if (u0 < u_end) fetch(u0, ka, va);
+    while (u0 < u_end) {
+        if (u0 + STEP < u_end) fetch(u0 + STEP, kb, vb);
+        work(u0, ka, va);
+        u0 += STEP;
+        if (u0 >= u_end) break;
+        if (u0 + STEP < u_end) fetch(u0 + STEP, ka, va);
+        work(u0, kb, vb);
+        u0 += STEP;
     }
 
-    __shared__ float s_m[GROUPS], s_l[GROUPS];
-    __shared__ float s_acc[GROUPS][DH];
-    if (tid % TPT == 0) { s_m[g] = m; s_l[g] = l; }
+    __shared__ float s_m[GQ][GROUPS], s_l[GQ][GROUPS];
+    __shared__ float s_acc[GQ][GROUPS][DH];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) s_acc[g][e0 + e] = acc[e];
+    for (int q = 0; q < GQ; ++q) {
+        if (tid % TPT == 0) { s_m[q][g] = m[q]; s_l[q][g] = l[q]; }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) s_acc[q][g][e0 + e] = acc[q][e];
+    }
     __syncthreads();
 
-    float M = -INFINITY, L = 0.f, O = 0.f;
-    if (tid < DH) {
+    if (tid >= DH) return;
 #pragma unroll
-        for (int i = 0; i < GROUPS; ++i) M = fmaxf(M, s_m[i]);
+    for (int q = 0; q < GQ; ++q) {
+        float M = -INFINITY, L = 0.f, O = 0.f;
+#pragma unroll
+        for (int i = 0; i < GROUPS; ++i) M = fmaxf(M, s_m[q][i]);
         if (M > -INFINITY) {
 #pragma unroll
             for (int i = 0; i < GROUPS; ++i) {
-                const float w = __expf(s_m[i] - M);  // empty groups: exp(-inf) = 0
-                L = fmaf(s_l[i], w, L);
-                O = fmaf(s_acc[i][tid], w, O);
+                const float w = __expf(s_m[q][i] - M);  // empty groups: exp(-inf) = 0
+                L = fmaf(s_l[q][i], w, L);
+                O = fmaf(s_acc[q][i][tid], w, O);
             }
         }
-    }
-    if (a.nsplit == 1) {
-        if (tid < DH) {
-            const size_t at = static_cast<size_t>(b) * a.hq * DH + h * DH + tid;
+        const int bh = b * a.hq + h0 + q;
+        if (a.nsplit == 1) {
+            const size_t at = static_cast<size_t>(bh) * DH + tid;
             if (a.o_dtype == DT_F32) static_cast<float*>(a.o)[at] = O / L;
             else static_cast<f16_t*>(a.o)[at] = static_cast<f16_t>(O / L);
+            continue;
         }
-        return;
-    }
-    const size_t pbase = static_cast<size_t>(bh) * a.nsplit;
-    if (tid < DH) a.part_o[(pbase + split) * DH + tid] = O;
-    if (tid == 0) {
-        a.part_ml[(pbase + split) * 2] = M;
-        a.part_ml[(pbase + split) * 2 + 1] = L;
+        const size_t pbase = static_cast<size_t>(bh) * a.nsplit;
+        a.part_o[(pbase + split) * DH + tid] = O;
+        if (tid == 0) {
+            a.part_ml[(pbase + split) * 2] = M;
+            a.part_ml[(pbase + split) * 2 + 1] = L;
+        }
     }
 }
 
@@ -485,26 +544,29 @@ __global__ __launch_bounds__(DH) void decode_attn_merge_kernel(DecodeAttn a) {
     else static_cast<f16_t*>(a.o)[at] = static_cast<f16_t>(ox / s_L);
 }
 
+// Query heads handled per workgroup: consecutive heads that share a KV head read its keys
+// and values once (grouped-query attention).
+int decode_attn_heads_per_group(int hq, int hkv) {
+    const int G = hq / hkv;
+    return G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1);
+}
+
+template <typename KT, int DH>
+static void launch_da(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st) {
+    const int gq = decode_attn_heads_per_group(a.hq, a.kv.hkv);
+    const dim3 grid(a.nsplit, a.nb * a.hq / gq), block(256);
+    if (gq == 4) launch((decode_attn_kernel<KT, DH, 4, 4>), grid, block, 0, st, a, sb);
+    else if (gq == 2) launch((decode_attn_kernel<KT, DH, 4, 2>), grid, block, 0, st, a, sb);
+    else launch((decode_attn_kernel<KT, DH, 4, 1>), grid, block, 0, st, a, sb);
+    if (a.nsplit > 1) launch(decode_attn_merge_kernel<DH>, dim3(a.nb * a.hq), dim3(DH), 0, st, a);
+}
+
 void launch_decode_attn(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st) {
-    const dim3 grid(a.nsplit, a.nb * a.hq), block(256);
     const bool f32 = a.kv_dtype == DT_F32;
-    const int units = a.nb * a.hq;
     switch (a.kv.dh) {
-        case 32:
-            if (f32) launch((decode_attn_kernel<float, 32, 4>), grid, block, 0, st, a, sb);
-            else launch((decode_attn_kernel<f16_t, 32, 4>), grid, block, 0, st, a, sb);
-            if (a.nsplit > 1) launch(decode_attn_merge_kernel<32>, dim3(units), dim3(32), 0, st, a);
-            break;
-        case 64:
-            if (f32) launch((decode_attn_kernel<float, 64, 4>), grid, block, 0, st, a, sb);
-            else launch((decode_attn_kernel<f16_t, 64, 4>), grid, block, 0, st, a, sb);
-            if (a.nsplit > 1) launch(decode_attn_merge_kernel<64>, dim3(units), dim3(64), 0, st, a);
-            break;
-        default:
-            if (f32) launch((decode_attn_kernel<float, 128, 4>), grid, block, 0, st, a, sb);
-            else launch((decode_attn_kernel<f16_t, 128, 4>), grid, block, 0, st, a, sb);
-            if (a.nsplit > 1) launch(decode_attn_merge_kernel<128>, dim3(units), dim3(128), 0, st, a);
-            break;
+        case 32: if (f32) launch_da<float, 32>(a, sb, st); else launch_da<f16_t, 32>(a, sb, st); break;
+        case 64: if (f32) launch_da<float, 64>(a, sb, st); else launch_da<f16_t, 64>(a, sb, st); break;
+        default: if (f32) launch_da<float, 128>(a, sb, st); else launch_da<f16_t, 128>(a, sb, st); break;
     }
 }
 

@@ -93,6 +93,25 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // Sequences of one call, passed by value in the kernel arguments.
+// Sum over groups of TPT adjacent lanes (TPT a power of two; groups aligned to TPT), the
+// result in every lane of the group.  Within a row of 16 lanes the exchanges are DPP
+// modifiers of the add itself (quad permutes, then the half-row and row mirrors), which cost
+// no LDS-crossbar instruction; only steps across rows use a shuffle.
+template <int CTRL>
+__device__ __forceinline__ float dpp_read(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+template <int TPT>
+__device__ __forceinline__ float group_sum(float v) {
+    if constexpr (TPT >= 2) v += dpp_read<0xB1>(v);    // quad_perm [1,0,3,2]
+    if constexpr (TPT >= 4) v += dpp_read<0x4E>(v);    // quad_perm [2,3,0,1]
+    if constexpr (TPT >= 8) v += dpp_read<0x141>(v);   // row_half_mirror
+    if constexpr (TPT >= 16) v += dpp_read<0x140>(v);  // row_mirror
+    if constexpr (TPT >= 32) v += __shfl_xor(v, 16, 64);
+    if constexpr (TPT >= 64) v += __shfl_xor(v, 32, 64);
+    return v;
+}
+
 // pos[b] = tokens already cached for seq[b] before this call.
 struct SeqBatch {
     int32_t n;

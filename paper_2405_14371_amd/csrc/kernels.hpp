@@ -109,6 +109,7 @@ struct DecodeAttn {
 };
 void launch_decode_attn(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st);
 // context tokens one workgroup of the decode attention kernel covers per trip
+int decode_attn_heads_per_group(int hq, int hkv);
 int decode_attn_tokens_per_trip(int kv_dtype, int dh);
 
 // rows of x [M, d] fp32 -> RMSNorm -> out [M, d] in out_dtype

@@ -276,60 +276,70 @@ void run_prefill(shard* s, const SeqBatch& sb, int T, const float* x_in, float* 
     }
 }
 
-// Context slices per (sequence, head): one trip of the kernel's token loop per slice,
-// unless that would put more than ~2048 workgroups on the device.
+// Context slices per workgroup unit (a sequence and the query heads that share its KV head):
+// enough slices to put about three workgroups on every compute unit, but never slices
+// shorter than one trip of the kernel's token loop (longer slices cost little: the trips of
+// a slice are software-pipelined).
 int pick_nsplit(const shard* s, const SeqBatch& sb) {
     int ctx = 1;
     for (int b = 0; b < sb.n; ++b) ctx = ctx > sb.pos[b] + 1 ? ctx : sb.pos[b] + 1;
-    const int units = sb.n * s->m.n_heads;
+    const int units = sb.n * s->m.n_heads / decode_attn_heads_per_group(s->m.n_heads, s->m.n_kv_heads);
     const int trip = decode_attn_tokens_per_trip(s->m.weight_dtype == SHARD_F32 ? DT_F32 : DT_F16, s->m.head_dim);
     int n = (ctx + trip - 1) / trip;
-    const int cap = (2048 + units - 1) / units;
-    if (n > cap) n = cap;
+    const int want = (768 + units - 1) / units;
+    if (n > want) n = want;
     if (n > s->nsplit_max) n = s->nsplit_max;
     return n < 1 ? 1 : n;
 }
 
-// Decode step for 9..16 sequences with bf16 weights: projections on the matrix cores, one
-// pass over the weights for the whole batch.
-void run_decode_mfma(shard* s, const SeqBatch& sb, const float* x_in, float* x_out, hipStream_t st) {
+// Decode step with 16-bit weights and more than 4 sequences: projections on the matrix
+// cores, one pass over the weights per group of up to 16 sequences (the streaming kernels'
+// vector ALUs fall behind the HBM stream from about 8 rows on).
+void run_decode_mfma(shard* s, const SeqBatch& all, const float* x_in, float* x_out, hipStream_t st) {
     const shard_model_cfg& m = s->m;
-    const int B = sb.n;
+    const int d_model = m.d_model;
     mark_layer(s, 0, st);
     for (int li = 0; li < s->L; ++li) {
         const LayerDev& l = s->layers[li];
-        const float* x = li == 0 ? x_in : x_out;
         const KvView kvv = kv_view(s, li);
-        DecodeLinear d{};
-        d.wt = DT_F16; d.nb = B; d.hq = m.n_heads; d.kv = kvv; d.rope = s->rope;
-        {
-            Bracket t(s, SHARD_K_DECODE_QKV, st);
-            launch_rmsnorm(x, l.g_attn, m.rms_eps, s->h, DT_F16, B, m.d_model, st);
-            d.W = l.wqkv; d.N = s->nqkv; d.K = m.d_model; d.xb = s->h; d.epi = EPI_QKV; d.q = s->q;
-            launch_decode_linear_mfma(d, sb, st);
-        }
-        {
-            DecodeAttn a{};
-            a.q = s->q; a.o = s->o; a.o_dtype = DT_F16; a.nb = B; a.hq = m.n_heads; a.kv_dtype = DT_F16; a.kv = kvv;
-            a.nsplit = pick_nsplit(s, sb); a.part_o = s->part_o; a.part_ml = s->part_ml;
-            Bracket t(s, SHARD_K_DECODE_ATTN, st);
-            launch_decode_attn(a, sb, st);
-        }
-        {
-            d.W = l.wo; d.N = m.d_model; d.K = s->nq; d.xb = s->o; d.epi = EPI_RESID; d.resid = x; d.out = x_out;
-            Bracket t(s, SHARD_K_DECODE_O, st);
-            launch_decode_linear_mfma(d, sb, st);
-        }
-        {
-            Bracket t(s, SHARD_K_DECODE_GATEUP, st);
-            launch_rmsnorm(x_out, l.g_ffn, m.rms_eps, s->h, DT_F16, B, m.d_model, st);
-            d.W = l.wgu; d.N = 2 * m.ffn_dim; d.K = m.d_model; d.xb = s->h; d.epi = EPI_SWIGLU; d.out_b = s->f;
-            launch_decode_linear_mfma(d, sb, st);
-        }
-        {
-            d.W = l.wd; d.N = m.d_model; d.K = m.ffn_dim; d.xb = s->f; d.epi = EPI_RESID; d.resid = x_out; d.out = x_out;
-            Bracket t(s, SHARD_K_DECODE_DOWN, st);
-            launch_decode_linear_mfma(d, sb, st);
+        for (int b0 = 0; b0 < all.n; b0 += 16) {
+            SeqBatch sb;
+            sb.n = all.n - b0 < 16 ? all.n - b0 : 16;
+            for (int i = 0; i < sb.n; ++i) { sb.seq[i] = all.seq[b0 + i]; sb.pos[i] = all.pos[b0 + i]; }
+            const int B = sb.n;
+            const float* x = (li == 0 ? x_in : x_out) + static_cast<size_t>(b0) * d_model;
+            float* y = x_out + static_cast<size_t>(b0) * d_model;
+            DecodeLinear d{};
+            d.wt = DT_F16; d.nb = B; d.hq = m.n_heads; d.kv = kvv; d.rope = s->rope;
+            {
+                Bracket t(s, SHARD_K_DECODE_QKV, st);
+                launch_rmsnorm(x, l.g_attn, m.rms_eps, s->h, DT_F16, B, d_model, st);
+                d.W = l.wqkv; d.N = s->nqkv; d.K = d_model; d.xb = s->h; d.epi = EPI_QKV; d.q = s->q;
+                launch_decode_linear_mfma(d, sb, st);
+            }
+            {
+                DecodeAttn a{};
+                a.q = s->q; a.o = s->o; a.o_dtype = DT_F16; a.nb = B; a.hq = m.n_heads; a.kv_dtype = DT_F16; a.kv = kvv;
+                a.nsplit = pick_nsplit(s, sb); a.part_o = s->part_o; a.part_ml = s->part_ml;
+                Bracket t(s, SHARD_K_DECODE_ATTN, st);
+                launch_decode_attn(a, sb, st);
+            }
+            {
+                d.W = l.wo; d.N = d_model; d.K = s->nq; d.xb = s->o; d.epi = EPI_RESID; d.resid = x; d.out = y;
+                Bracket t(s, SHARD_K_DECODE_O, st);
+                launch_decode_linear_mfma(d, sb, st);
+            }
+            {
+                Bracket t(s, SHARD_K_DECODE_GATEUP, st);
+                launch_rmsnorm(y, l.g_ffn, m.rms_eps, s->h, DT_F16, B, d_model, st);
+                d.W = l.wgu; d.N = 2 * m.ffn_dim; d.K = d_model; d.xb = s->h; d.epi = EPI_SWIGLU; d.out_b = s->f;
+                launch_decode_linear_mfma(d, sb, st);
+            }
+            {
+                d.W = l.wd; d.N = d_model; d.K = m.ffn_dim; d.xb = s->f; d.epi = EPI_RESID; d.resid = y; d.out = y;
+                Bracket t(s, SHARD_K_DECODE_DOWN, st);
+                launch_decode_linear_mfma(d, sb, st);
+            }
         }
         mark_layer(s, li + 1, st);
     }
@@ -339,7 +349,7 @@ void run_decode(shard* s, const SeqBatch& sb, const float* x_in, float* x_out, h
     const shard_model_cfg& m = s->m;
     const int dt = m.weight_dtype == SHARD_F32 ? DT_F32 : DT_F16;
     const int B = sb.n;
-    if (dt == DT_F16 && B > 8 && B <= 16 && m.d_model % 64 == 0 && m.ffn_dim % 64 == 0 && s->nq % 64 == 0) {
+    if (dt == DT_F16 && B > 4 && m.d_model % 64 == 0 && m.ffn_dim % 64 == 0 && s->nq % 64 == 0) {
         run_decode_mfma(s, sb, x_in, x_out, st);
         return;
     }

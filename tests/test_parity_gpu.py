@@ -60,10 +60,11 @@ def test_head_dim_128_and_wide_batch_decode(lib):
     run_case(lib, cfg, 2, "f32", B=16, T=20, n_dec=3, seed=7)
 
 
-@pytest.mark.parametrize("B", [9, 16])
-def test_bf16_batches_of_9_to_16_decode_on_matrix_cores(lib, B):
-    """bf16 decode batches above 8 rows take the MFMA projection kernels (one pass over the
-    weights); GQA, random gains, ragged page use."""
+@pytest.mark.parametrize("B", [5, 8, 9, 16, 17, 40])
+def test_bf16_batches_above_4_decode_on_matrix_cores(lib, B):
+    """bf16 decode batches of more than 4 rows take the MFMA projection kernels, one pass over
+    the weights per group of up to 16 sequences (17 and 40: a ragged last group); GQA, random
+    gains, ragged page use."""
     cfg = synth.model_cfg("tiny", d_model=512, n_heads=8, n_kv_heads=2, head_dim=64, ffn_dim=1024)
     run_case(lib, cfg, 2, "bf16", B=B, T=19, n_dec=4, seed=21, gains=True, page_size=16)
 
