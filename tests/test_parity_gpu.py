@@ -225,3 +225,57 @@ def test_profile_and_kernel_timing(lib):
     assert all(v["seconds"] > 0 for k, v in t.items() if v["launches"])
     sh.timing_enable(False)
     sh.close()
+
+
+def _sweep_cases():
+    """Seeded shapes chosen to land on every tile variant and tail of the prefill kernels:
+    query blocks of 128 with ragged ends, key blocks of 32, contexts that start above zero,
+    head sizes 64 and 128 (LDS-staged attention) and 32 (per-wave attention), K multiples and
+    non-multiples of the direct-to-LDS k-step, page sizes that divide nothing."""
+    rng = np.random.default_rng(2024)
+    cases = []
+    for i in range(10):
+        dh = int(rng.choice([32, 64, 128]))
+        hkv = int(rng.choice([1, 2, 4]))
+        hq = hkv * int(rng.choice([1, 2, 4]))
+        d = int(rng.choice([128, 192, 256, 320]))
+        ffn = int(rng.choice([344, 512, 688, 1000]))
+        cases.append(dict(dtype="f32" if i % 2 == 0 else "bf16", d_model=d, n_heads=hq, n_kv_heads=hkv, head_dim=dh,
+                          ffn_dim=ffn, B=int(rng.integers(1, 4)), T0=int(rng.integers(1, 200)),
+                          T1=int(rng.integers(1, 300)), n_dec=2, page=int(rng.choice([1, 5, 16, 64])), seed=100 + i))
+    cases.append(dict(dtype="f32", d_model=256, n_heads=4, n_kv_heads=2, head_dim=128, ffn_dim=688, B=2, T0=130, T1=259,
+                      n_dec=2, page=16, seed=120))
+    cases.append(dict(dtype="bf16", d_model=512, n_heads=8, n_kv_heads=1, head_dim=128, ffn_dim=1000, B=1, T0=1, T1=385,
+                      n_dec=2, page=1, seed=121))
+    return cases
+
+
+@pytest.mark.parametrize("case", _sweep_cases(), ids=lambda c: f"{c['dtype']}-d{c['d_model']}-h{c['n_heads']}x{c['head_dim']}-kv{c['n_kv_heads']}-T{c['T0']}+{c['T1']}-p{c['page']}")
+def test_seeded_shape_sweep_two_prefill_chunks_then_decode(lib, case):
+    c = case
+    cfg = synth.model_cfg("tiny", d_model=c["d_model"], n_heads=c["n_heads"], n_kv_heads=c["n_kv_heads"],
+                          head_dim=c["head_dim"], ffn_dim=c["ffn_dim"])
+    B, T0, T1 = c["B"], c["T0"], c["T1"]
+    layers = H.make_layers(cfg, c["seed"], 2, c["dtype"], gains=True)
+    sh = H.gpu_shard(lib, cfg, layers, c["dtype"], max_seqs=B, max_seq_len=T0 + T1 + c["n_dec"],
+                     page_size=c["page"], max_batch_tokens=B * max(T0, T1))
+    ids = [sh.seq_alloc() for _ in range(B)]
+    chunks = [np.concatenate([synth.hidden_states(cfg, c["seed"], "prefill", k, b, 1, T) for b in range(B)])
+              for k, T in enumerate((T0, T1))]
+    chunks += [np.concatenate([synth.hidden_states(cfg, c["seed"], "dec", s, b, 1, 1) for b in range(B)])
+               for s in range(c["n_dec"])]
+    # the second chunk is a prefill on a non-empty cache (its first chunk may even be one token)
+    torch = H.torch_mod()
+    got = []
+    st = torch.cuda.current_stream().cuda_stream
+    for k, x in enumerate(chunks):
+        xd = H.to_dev(x); yd = torch.empty_like(xd)
+        if k < 2:
+            sh.prefill(ids, x.shape[1], xd, yd, st)
+        else:
+            sh.decode(ids, xd, yd, st)
+        torch.cuda.synchronize()
+        got.append(yd.cpu().numpy())
+    want = H.run_oracle(cfg, layers, chunks)
+    H.assert_parity(got, want, H.TOL[c["dtype"]], str(c))
+    sh.close()
