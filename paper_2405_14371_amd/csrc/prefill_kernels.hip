@@ -465,12 +465,14 @@ static void launch_gemm_f16(const PrefillGemm& a, const SeqBatch& sb, hipStream_
         static const GemmVariant v[] = {{256, 256, 1, {1500.f, 0.f, 0.f}},
                                         {256, 128, 1, {1250.f, 0.f, 0.f}},
                                         {128, 128, 1, {1000.f, 0.f, 0.f}},
-                                        {128, 64, 2, {650.f, 900.f, 0.f}}};
-        switch (pick_variant(v, 4, a.M, a.N)) {
+                                        {128, 64, 2, {650.f, 900.f, 0.f}},
+                                        {384, 128, 1, {1300.f, 0.f, 0.f}}};  // 256 tiles for 12288 x 1024
+        switch (pick_variant(v, 5, a.M, a.N)) {
             case 0: launch_gemm_dma<f16_t, 256, 256, 32, 2, 4, 2>(a, sb, st); break;
             case 1: launch_gemm_dma<f16_t, 256, 128, 32, 3, 4, 2>(a, sb, st); break;
             case 2: launch_gemm_dma<f16_t, 128, 128, 32, 3, 2, 2>(a, sb, st); break;
-            default: launch_gemm_dma<f16_t, 128, 64, 32, 3, 2, 2>(a, sb, st); break;
+            case 3: launch_gemm_dma<f16_t, 128, 64, 32, 3, 2, 2>(a, sb, st); break;
+            default: launch_gemm_dma<f16_t, 384, 128, 32, 2, 4, 2>(a, sb, st); break;
         }
         return;
     }
