@@ -201,15 +201,16 @@ void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t
 }
 
 // ---------------------------------------------------------------------------------------
-// Linear layer for 9..16 activation rows with 16-bit weights: at 16 FMAs per weight element
-// the vector ALUs could no longer keep up with the HBM stream, so the products run on the
-// matrix cores: D[n][b] = sum_k W[n][k] x[b][k] with v_mfma_f32_16x16x32_bf16, the 16
-// activation rows filling the MFMA's second dimension exactly.
-// A workgroup owns 16 or 32 consecutive rows of W (one or two MFMA row tiles); its four waves split K
-// in interleaved 64-element blocks and meet in LDS (fixed order).  Lane (row = lane%16,
-// g = lane/16) supplies elements 32*j + 8*g + (0..7) of a block to MFMA j on both operands,
-// so every load instruction reads 64 contiguous bytes per row.  Activations arrive already
-// rounded to half (and normalised where the step needs it).
+// Linear layer for up to 16 activation rows with half weights: from about 8 rows on (16 FMAs
+// per weight element at 16) the vector ALUs could no longer keep up with the HBM stream, so
+// the products run on the matrix cores: D[n][b] = sum_k W[n][k] x[b][k] with
+// v_mfma_f32_16x16x32_f16, the activation rows filling the MFMA's second dimension (rows past
+// the batch are zero).
+// A workgroup owns 16 * TILES consecutive rows of W; its WAVES waves split K in interleaved
+// 64-element blocks, U of them in flight per wave, and meet in LDS (fixed order).  Lane
+// (row = lane%16, g = lane/16) supplies elements 32*j + 8*g + (0..7) of a block to MFMA j on
+// both operands, so every load instruction reads 64 contiguous bytes per row.  Activations
+// arrive already rounded to half (and normalised where the step needs it).
 // ---------------------------------------------------------------------------------------
 typedef _Float16 f16x8_d __attribute__((ext_vector_type(8)));
 typedef float f32x4_d __attribute__((ext_vector_type(4)));

@@ -1,26 +1,15 @@
-// Small device-side helpers shared by the gfx950 kernels: bf16 <-> fp32, 16-byte typed
-// loads widened to fp32, wavefront (64-lane) reductions.
+// Small device-side helpers shared by the gfx950 kernels: element types, 16-byte typed
+// loads widened to fp32, wavefront (64-lane) and lane-group reductions.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 namespace shk {
 
-typedef uint16_t bf16_t;  // raw bf16 bit pattern (weights as the caller supplies them)
 typedef _Float16 f16_t;   // IEEE half: the 16-bit format of activations and of the KV cache
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-__device__ __forceinline__ float bf16_to_f32(bf16_t v) {
-    return __uint_as_float(static_cast<uint32_t>(v) << 16);
-}
-// round-to-nearest-even; inputs here are finite
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return static_cast<bf16_t>(u >> 16);
-}
 
 template <typename T> struct Elem;
 template <> struct Elem<float> {
@@ -28,12 +17,6 @@ template <> struct Elem<float> {
     __device__ static __forceinline__ float to_f32(float v) { return v; }
     __device__ static __forceinline__ float from_f32(float v) { return v; }
 };
-template <> struct Elem<bf16_t> {
-    static constexpr int VEC = 8;
-    __device__ static __forceinline__ float to_f32(bf16_t v) { return bf16_to_f32(v); }
-    __device__ static __forceinline__ bf16_t from_f32(float v) { return f32_to_bf16(v); }
-};
-
 template <> struct Elem<f16_t> {
     static constexpr int VEC = 8;
     __device__ static __forceinline__ float to_f32(f16_t v) { return static_cast<float>(v); }
@@ -45,7 +28,7 @@ template <typename WT> struct ActOf;
 template <> struct ActOf<float> { typedef float type; };
 template <> struct ActOf<f16_t> { typedef f16_t type; };
 
-// Load 16 bytes at p (16-byte aligned) and widen to fp32: 4 floats or 8 bf16.
+// Load 16 bytes at p (16-byte aligned) and widen to fp32: 4 floats or 8 halfs.
 template <typename T> struct Vec16;
 // load_stream: the same with a non-temporal hint, for data read exactly once (weights of the
 // autoregressive phase) - measured 4-6 % faster streams than plain loads on MI355X.

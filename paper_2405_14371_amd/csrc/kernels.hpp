@@ -75,7 +75,7 @@ struct DecodeLinear {
     const void* W;
     int32_t N, K;
     int32_t wt;            // DType of W
-    int32_t nb;            // activation rows, 1..8
+    int32_t nb;            // activation rows, 1..8 (matrix-core variant: 1..16)
     const float* x;        // [nb, K]
     const float* gain;     // non-null: RMSNorm(x; gain, eps) is applied to x on the fly
     float eps;
@@ -88,7 +88,7 @@ struct DecodeLinear {
     int32_t hq;
     KvView kv;
     const float2* rope;    // [max_seq_len, dh/2] (cos, sin)
-    // matrix-core variant (launch_decode_linear_mfma): bf16 weights, 9..16 rows
+    // matrix-core variant (launch_decode_linear_mfma): half weights, up to 16 rows
     const void* xb;        // [nb, K] half activations (already normalised where needed)
     void* out_b;           // EPI_SWIGLU output [nb, N/2] half
 };
