@@ -67,12 +67,13 @@ def algorithmic_work(cfg, wl):
 
 
 def cpu_baseline(cfg, wl, seed):
-    """Time the oracle, as it stands, on a bounded sample: 2 layers of the workload's layer
-    shape, a 32-token prefill and 6 decode steps; scale per-layer times to the shard."""
+    """Time the oracle, as it stands, on a bounded sample (10-20 s of host work at the 7B
+    shape): 2 layers of the workload's layer shape, a 128-token prefill and 64 decode steps;
+    scale per-layer times to the shard."""
     from threadpoolctl import threadpool_info
     from oracle import llama_shard as orc
     from paper_2405_14371_amd import synth
-    n_l, t_pre, n_dec = min(2, wl["layers"]), min(32, wl["T"]), 6
+    n_l, t_pre, n_dec = min(2, wl["layers"]), min(128, wl["T"]), min(64, wl["n_dec"])
     layers = synth.shard_weights(cfg, seed, 0, n_l, wl["dtype"])
     o = orc.OracleShard(cfg, layers, keep_f64=True)
     x = synth.hidden_states(cfg, seed, "prefill", 0, 0, 1, t_pre)[0].astype(np.float64)
@@ -207,7 +208,7 @@ def main():
     gm_flops = sum(work["gemm_flops"].values()) * L * MB
     peak_tf = MFMA_PEAK_TFLOPS[wl["dtype"]]
     roofline_prefill = {
-        "kernel": "gemm_kernel (MFMA projections of shard_prefill)",
+        "kernel": "gemm_dma_kernel (MFMA projections of shard_prefill)",
         "bound": "mfma", "achieved": round(gm_flops / gm["seconds"] / 1e12, 2), "peak": peak_tf, "unit": "TFLOP/s",
         "frac": round(gm_flops / gm["seconds"] / 1e12 / peak_tf, 4),
         "launches": gm["launches"], "avg_launch_us": round(gm["seconds"] / max(1, gm["launches"]) * 1e6, 2),
