@@ -26,6 +26,13 @@
  *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream).  Work is
  *    enqueued on it and the call returns without waiting; the caller synchronises.
  *  - A shard handle is not thread-safe; use one thread per handle at a time.
+ *  - Several streams: calls issued (from that one thread) on different streams may overlap on
+ *    the device when they carry different sequences - micro-batches of a pipeline stage, for
+ *    instance.  The shard keeps SHARD_MAX_STREAMS workspace sets (one large enough for
+ *    prefill) and orders its own reuse of them with events, so any pattern of streams is
+ *    safe; up to SHARD_MAX_STREAMS decode streams, or one prefill next to decode streams, run
+ *    without waiting for each other.  The caller orders calls that touch the SAME sequence
+ *    (its decode after its prefill, step after step), as on a single stream.
  */
 #ifndef SHARD_H
 #define SHARD_H
@@ -51,6 +58,8 @@ enum { SHARD_F32 = 0, SHARD_BF16 = 1 };
 
 /* Largest number of sequences one shard_prefill / shard_decode call may carry. */
 #define SHARD_MAX_BATCH 64
+/* Workspace sets a shard keeps, i.e. streams whose shard_decode calls can overlap. */
+#define SHARD_MAX_STREAMS 4
 
 typedef struct {
     int32_t d_model;      /* width of the hidden state */

@@ -78,13 +78,23 @@ struct shard {
     std::vector<int32_t> seq_len;    // -1 = slot not live
     std::vector<int32_t> seq_pages;  // pages held per slot
     std::vector<int32_t> host_table; // mirror of block_table
-    // workspace
-    void* h = nullptr;     // [mmax, d]      normalised activations (weight dtype)
-    float* q = nullptr;    // [mmax, Hq*dh]
-    void* o = nullptr;     // [mmax, Hq*dh]  attention output (fp32 in decode, weight dtype in prefill)
-    void* f = nullptr;     // [mmax, F]      SwiGLU output   (same)
-    float* part_o = nullptr;
-    float* part_ml = nullptr;
+    // Workspaces.  Set 0 holds mmax rows (prefill); the others hold SHARD_MAX_BATCH rows and let
+    // decode calls on different streams run side by side.  A set belongs to the stream that
+    // used it last; another stream takes it over only after waiting for that use (an event).
+    struct Work {
+        void* h = nullptr;     // [rows, d]      normalised activations (weight dtype)
+        float* q = nullptr;    // [rows, Hq*dh]
+        void* o = nullptr;     // [rows, Hq*dh]  attention output (fp32 in decode, weight dtype in prefill)
+        void* f = nullptr;     // [rows, F]      SwiGLU output   (same)
+        float* part_o = nullptr;
+        float* part_ml = nullptr;
+        hipStream_t owner = nullptr;
+        bool used = false;
+        uint64_t last_use = 0;
+        hipEvent_t done = nullptr;  // recorded after every use
+    };
+    Work work[SHARD_MAX_STREAMS];
+    uint64_t use_clock = 0;
     int nsplit_max = 32;
     Timing timing;
     uint32_t* cvt_flag = nullptr;   // overflow flag of the bf16 -> half conversion during create
@@ -100,9 +110,15 @@ void free_all(shard* s) {
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
     }
-    void* ptrs[] = {s->rope, s->block_table, s->h, s->q, s->o, s->f, s->part_o, s->part_ml, s->cvt_flag};
+    void* ptrs[] = {s->rope, s->block_table, s->cvt_flag};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
+    for (auto& w : s->work) {
+        void* wp[] = {w.h, w.q, w.o, w.f, w.part_o, w.part_ml};
+        for (void* p : wp)
+            if (p) (void)hipFree(p);
+        if (w.done) (void)hipEventDestroy(w.done);
+    }
     for (auto& v : s->timing.ev)
         for (hipEvent_t e : v) (void)hipEventDestroy(e);
     for (hipEvent_t e : s->layer_ev) (void)hipEventDestroy(e);
@@ -226,7 +242,7 @@ void mark_layer(shard* s, int i, hipStream_t st) {
     if (s->record_layers) (void)hipEventRecord(s->layer_ev[i], st);
 }
 
-void run_prefill(shard* s, const SeqBatch& sb, int T, const float* x_in, float* x_out, hipStream_t st) {
+void run_prefill(shard* s, shard::Work& wk, const SeqBatch& sb, int T, const float* x_in, float* x_out, hipStream_t st) {
     const shard_model_cfg& m = s->m;
     const int M = sb.n * T;
     const int dt = m.weight_dtype == SHARD_F32 ? DT_F32 : DT_F16;    // weights as stored on the device
@@ -237,37 +253,37 @@ void run_prefill(shard* s, const SeqBatch& sb, int T, const float* x_in, float* 
         const float* x = li == 0 ? x_in : x_out;
         {
             Bracket t(s, SHARD_K_PREFILL_NORM, st);
-            launch_rmsnorm(x, l.g_attn, m.rms_eps, s->h, adt, M, m.d_model, st);
+            launch_rmsnorm(x, l.g_attn, m.rms_eps, wk.h, adt, M, m.d_model, st);
         }
         PrefillGemm g{};
         g.M = M; g.dt = dt; g.T = T; g.hq = m.n_heads; g.kv = kv_view(s, li); g.rope = s->rope;
-        g.A = s->h; g.W = l.wqkv; g.N = s->nqkv; g.K = m.d_model; g.epi = EPI_QKV; g.q = s->q;
+        g.A = wk.h; g.W = l.wqkv; g.N = s->nqkv; g.K = m.d_model; g.epi = EPI_QKV; g.q = wk.q;
         {
             Bracket t(s, SHARD_K_PREFILL_QKV, st);
             launch_prefill_gemm(g, sb, st);
         }
         PrefillAttn at{};
-        at.q = s->q; at.o = s->o; at.out_dtype = adt; at.B = sb.n; at.T = T; at.hq = m.n_heads;
+        at.q = wk.q; at.o = wk.o; at.out_dtype = adt; at.B = sb.n; at.T = T; at.hq = m.n_heads;
         at.kv_dtype = adt; at.kv = g.kv;
         {
             Bracket t(s, SHARD_K_PREFILL_ATTN, st);
             launch_prefill_attn(at, sb, st);
         }
-        g.A = s->o; g.W = l.wo; g.N = m.d_model; g.K = s->nq; g.epi = EPI_RESID; g.resid = x; g.out = x_out;
+        g.A = wk.o; g.W = l.wo; g.N = m.d_model; g.K = s->nq; g.epi = EPI_RESID; g.resid = x; g.out = x_out;
         {
             Bracket t(s, SHARD_K_PREFILL_O, st);
             launch_prefill_gemm(g, sb, st);
         }
         {
             Bracket t(s, SHARD_K_PREFILL_NORM, st);
-            launch_rmsnorm(x_out, l.g_ffn, m.rms_eps, s->h, adt, M, m.d_model, st);
+            launch_rmsnorm(x_out, l.g_ffn, m.rms_eps, wk.h, adt, M, m.d_model, st);
         }
-        g.A = s->h; g.W = l.wgu; g.N = 2 * m.ffn_dim; g.K = m.d_model; g.epi = EPI_SWIGLU; g.out_act = s->f;
+        g.A = wk.h; g.W = l.wgu; g.N = 2 * m.ffn_dim; g.K = m.d_model; g.epi = EPI_SWIGLU; g.out_act = wk.f;
         {
             Bracket t(s, SHARD_K_PREFILL_GATEUP, st);
             launch_prefill_gemm(g, sb, st);
         }
-        g.A = s->f; g.W = l.wd; g.N = m.d_model; g.K = m.ffn_dim; g.epi = EPI_RESID; g.resid = x_out; g.out = x_out;
+        g.A = wk.f; g.W = l.wd; g.N = m.d_model; g.K = m.ffn_dim; g.epi = EPI_RESID; g.resid = x_out; g.out = x_out;
         {
             Bracket t(s, SHARD_K_PREFILL_DOWN, st);
             launch_prefill_gemm(g, sb, st);
@@ -295,7 +311,7 @@ int pick_nsplit(const shard* s, const SeqBatch& sb) {
 // Decode step with 16-bit weights and more than 4 sequences: projections on the matrix
 // cores, one pass over the weights per group of up to 16 sequences (the streaming kernels'
 // vector ALUs fall behind the HBM stream from about 8 rows on).
-void run_decode_mfma(shard* s, const SeqBatch& all, const float* x_in, float* x_out, hipStream_t st) {
+void run_decode_mfma(shard* s, shard::Work& wk, const SeqBatch& all, const float* x_in, float* x_out, hipStream_t st) {
     const shard_model_cfg& m = s->m;
     const int d_model = m.d_model;
     mark_layer(s, 0, st);
@@ -313,30 +329,30 @@ void run_decode_mfma(shard* s, const SeqBatch& all, const float* x_in, float* x_
             d.wt = DT_F16; d.nb = B; d.hq = m.n_heads; d.kv = kvv; d.rope = s->rope;
             {
                 Bracket t(s, SHARD_K_DECODE_QKV, st);
-                launch_rmsnorm(x, l.g_attn, m.rms_eps, s->h, DT_F16, B, d_model, st);
-                d.W = l.wqkv; d.N = s->nqkv; d.K = d_model; d.xb = s->h; d.epi = EPI_QKV; d.q = s->q;
+                launch_rmsnorm(x, l.g_attn, m.rms_eps, wk.h, DT_F16, B, d_model, st);
+                d.W = l.wqkv; d.N = s->nqkv; d.K = d_model; d.xb = wk.h; d.epi = EPI_QKV; d.q = wk.q;
                 launch_decode_linear_mfma(d, sb, st);
             }
             {
                 DecodeAttn a{};
-                a.q = s->q; a.o = s->o; a.o_dtype = DT_F16; a.nb = B; a.hq = m.n_heads; a.kv_dtype = DT_F16; a.kv = kvv;
-                a.nsplit = pick_nsplit(s, sb); a.part_o = s->part_o; a.part_ml = s->part_ml;
+                a.q = wk.q; a.o = wk.o; a.o_dtype = DT_F16; a.nb = B; a.hq = m.n_heads; a.kv_dtype = DT_F16; a.kv = kvv;
+                a.nsplit = pick_nsplit(s, sb); a.part_o = wk.part_o; a.part_ml = wk.part_ml;
                 Bracket t(s, SHARD_K_DECODE_ATTN, st);
                 launch_decode_attn(a, sb, st);
             }
             {
-                d.W = l.wo; d.N = d_model; d.K = s->nq; d.xb = s->o; d.epi = EPI_RESID; d.resid = x; d.out = y;
+                d.W = l.wo; d.N = d_model; d.K = s->nq; d.xb = wk.o; d.epi = EPI_RESID; d.resid = x; d.out = y;
                 Bracket t(s, SHARD_K_DECODE_O, st);
                 launch_decode_linear_mfma(d, sb, st);
             }
             {
                 Bracket t(s, SHARD_K_DECODE_GATEUP, st);
-                launch_rmsnorm(y, l.g_ffn, m.rms_eps, s->h, DT_F16, B, d_model, st);
-                d.W = l.wgu; d.N = 2 * m.ffn_dim; d.K = d_model; d.xb = s->h; d.epi = EPI_SWIGLU; d.out_b = s->f;
+                launch_rmsnorm(y, l.g_ffn, m.rms_eps, wk.h, DT_F16, B, d_model, st);
+                d.W = l.wgu; d.N = 2 * m.ffn_dim; d.K = d_model; d.xb = wk.h; d.epi = EPI_SWIGLU; d.out_b = wk.f;
                 launch_decode_linear_mfma(d, sb, st);
             }
             {
-                d.W = l.wd; d.N = d_model; d.K = m.ffn_dim; d.xb = s->f; d.epi = EPI_RESID; d.resid = y; d.out = y;
+                d.W = l.wd; d.N = d_model; d.K = m.ffn_dim; d.xb = wk.f; d.epi = EPI_RESID; d.resid = y; d.out = y;
                 Bracket t(s, SHARD_K_DECODE_DOWN, st);
                 launch_decode_linear_mfma(d, sb, st);
             }
@@ -345,16 +361,16 @@ void run_decode_mfma(shard* s, const SeqBatch& all, const float* x_in, float* x_
     }
 }
 
-void run_decode(shard* s, const SeqBatch& sb, const float* x_in, float* x_out, hipStream_t st) {
+void run_decode(shard* s, shard::Work& wk, const SeqBatch& sb, const float* x_in, float* x_out, hipStream_t st) {
     const shard_model_cfg& m = s->m;
     const int dt = m.weight_dtype == SHARD_F32 ? DT_F32 : DT_F16;
     const int B = sb.n;
     if (dt == DT_F16 && B > 4 && m.d_model % 64 == 0 && m.ffn_dim % 64 == 0 && s->nq % 64 == 0) {
-        run_decode_mfma(s, sb, x_in, x_out, st);
+        run_decode_mfma(s, wk, sb, x_in, x_out, st);
         return;
     }
-    float* o = static_cast<float*>(s->o);
-    float* f = static_cast<float*>(s->f);
+    float* o = static_cast<float*>(wk.o);
+    float* f = static_cast<float*>(wk.f);
     mark_layer(s, 0, st);
     for (int li = 0; li < s->L; ++li) {
         const LayerDev& l = s->layers[li];
@@ -369,15 +385,15 @@ void run_decode(shard* s, const SeqBatch& sb, const float* x_in, float* x_out, h
             DecodeLinear d{};
             d.W = l.wqkv; d.N = s->nqkv; d.K = m.d_model; d.wt = dt; d.nb = nb;
             d.x = x + static_cast<size_t>(b0) * m.d_model; d.gain = l.g_attn; d.eps = m.rms_eps;
-            d.epi = EPI_QKV; d.q = s->q + static_cast<size_t>(b0) * s->nq; d.hq = m.n_heads; d.kv = kvv; d.rope = s->rope;
+            d.epi = EPI_QKV; d.q = wk.q + static_cast<size_t>(b0) * s->nq; d.hq = m.n_heads; d.kv = kvv; d.rope = s->rope;
             Bracket t(s, SHARD_K_DECODE_QKV, st);
             launch_decode_linear(d, sub, st);
         }
         {
             DecodeAttn a{};
-            a.q = s->q; a.o = o; a.o_dtype = DT_F32; a.nb = B; a.hq = m.n_heads;
+            a.q = wk.q; a.o = o; a.o_dtype = DT_F32; a.nb = B; a.hq = m.n_heads;
             a.kv_dtype = dt; a.kv = kvv;
-            a.nsplit = pick_nsplit(s, sb); a.part_o = s->part_o; a.part_ml = s->part_ml;
+            a.nsplit = pick_nsplit(s, sb); a.part_o = wk.part_o; a.part_ml = wk.part_ml;
             Bracket t(s, SHARD_K_DECODE_ATTN, st);
             launch_decode_attn(a, sb, st);
         }
@@ -410,6 +426,39 @@ void run_decode(shard* s, const SeqBatch& sb, const float* x_in, float* x_out, h
         }
         mark_layer(s, li + 1, st);
     }
+}
+
+// The workspace set a call on stream `st` uses.  Prefill always takes set 0 (the only one with
+// mmax rows); decode prefers a set the stream already owns, then a free small set, then set 0,
+// then the least recently used one.  Taking over another stream's set first makes `st` wait
+// for that stream's last use of it.
+int acquire_work(shard* s, hipStream_t st, bool prefill, shard::Work** out) {
+    shard::Work* w = nullptr;
+    if (prefill) {
+        w = &s->work[0];
+    } else {
+        for (auto& c : s->work)
+            if (c.used && c.owner == st) { w = &c; break; }
+        for (int i = 1; !w && i < SHARD_MAX_STREAMS; ++i)
+            if (!s->work[i].used) w = &s->work[i];
+        if (!w && !s->work[0].used) w = &s->work[0];
+        if (!w) {
+            w = &s->work[0];
+            for (auto& c : s->work)
+                if (c.last_use < w->last_use) w = &c;
+        }
+    }
+    if (w->used && w->owner != st) HIP_TRY(hipStreamWaitEvent(st, w->done, 0));
+    w->owner = st;
+    w->used = true;
+    w->last_use = ++s->use_clock;
+    *out = w;
+    return SHARD_OK;
+}
+
+int release_work(shard::Work* w, hipStream_t st) {
+    HIP_TRY(hipEventRecord(w->done, st));
+    return SHARD_OK;
 }
 
 int check_launch() {
@@ -527,14 +576,18 @@ int shard_create(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg
     s->seq_len.assign(kv->max_seqs, -1);
     s->seq_pages.assign(kv->max_seqs, 0);
 
-    const size_t mm = s->mmax;
-    CREATE_TRY(hipMalloc(&s->h, mm * d * es));
-    CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&s->q), mm * s->nq * sizeof(float)));
-    CREATE_TRY(hipMalloc(&s->o, mm * s->nq * sizeof(float)));
-    CREATE_TRY(hipMalloc(&s->f, mm * F * sizeof(float)));
     const size_t units = static_cast<size_t>(SHARD_MAX_BATCH) * model->n_heads;
-    CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&s->part_o), units * s->nsplit_max * dh * sizeof(float)));
-    CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&s->part_ml), units * s->nsplit_max * 2 * sizeof(float)));
+    for (int wi = 0; wi < SHARD_MAX_STREAMS; ++wi) {
+        shard::Work& w = s->work[wi];
+        const size_t rows = wi == 0 ? static_cast<size_t>(s->mmax) : static_cast<size_t>(SHARD_MAX_BATCH);
+        CREATE_TRY(hipMalloc(&w.h, rows * d * es));
+        CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&w.q), rows * s->nq * sizeof(float)));
+        CREATE_TRY(hipMalloc(&w.o, rows * s->nq * sizeof(float)));
+        CREATE_TRY(hipMalloc(&w.f, rows * F * sizeof(float)));
+        CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&w.part_o), units * s->nsplit_max * dh * sizeof(float)));
+        CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&w.part_ml), units * s->nsplit_max * 2 * sizeof(float)));
+        CREATE_TRY(hipEventCreateWithFlags(&w.done, hipEventDisableTiming));
+    }
     s->layer_ev.resize(L + 1);
     for (auto& e : s->layer_ev) e = nullptr;
     for (auto& e : s->layer_ev) CREATE_TRY(hipEventCreate(&e));
@@ -600,10 +653,14 @@ int shard_prefill(shard_t* s, const int32_t* seq_ids, int32_t B, int32_t T, cons
     if (rc) return rc;
     if (!x_in || !x_out) return fail(SHARD_E_INVAL, "null activation pointer");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    shard::Work* wk = nullptr;
+    rc = acquire_work(s, st, true, &wk);
+    if (rc) return rc;
     grow_sequences(s, sb, T, st);
-    run_prefill(s, sb, T, static_cast<const float*>(x_in), static_cast<float*>(x_out), st);
+    run_prefill(s, *wk, sb, T, static_cast<const float*>(x_in), static_cast<float*>(x_out), st);
     for (int b = 0; b < B; ++b) s->seq_len[sb.seq[b]] += T;
-    return check_launch();
+    rc = release_work(wk, st);
+    return rc ? rc : check_launch();
 }
 
 int shard_decode(shard_t* s, const int32_t* seq_ids, int32_t B, const void* x_in, void* x_out, void* hip_stream) {
@@ -612,10 +669,14 @@ int shard_decode(shard_t* s, const int32_t* seq_ids, int32_t B, const void* x_in
     if (rc) return rc;
     if (!x_in || !x_out) return fail(SHARD_E_INVAL, "null activation pointer");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    shard::Work* wk = nullptr;
+    rc = acquire_work(s, st, false, &wk);
+    if (rc) return rc;
     grow_sequences(s, sb, 1, st);
-    run_decode(s, sb, static_cast<const float*>(x_in), static_cast<float*>(x_out), st);
+    run_decode(s, *wk, sb, static_cast<const float*>(x_in), static_cast<float*>(x_out), st);
     for (int b = 0; b < B; ++b) s->seq_len[sb.seq[b]] += 1;
-    return check_launch();
+    rc = release_work(wk, st);
+    return rc ? rc : check_launch();
 }
 
 int shard_timing_enable(shard_t* s, int32_t on) {
@@ -633,7 +694,7 @@ int shard_timing_enable(shard_t* s, int32_t on) {
 int shard_timing_read(shard_t* s, int64_t launches[SHARD_K_COUNT], double seconds[SHARD_K_COUNT]) {
     if (!s || !launches || !seconds) return fail(SHARD_E_INVAL, "null argument");
     Timing& t = s->timing;
-    HIP_TRY(hipStreamSynchronize(t.last_stream));
+    HIP_TRY(hipDeviceSynchronize());  // timed launches may sit on several streams
     for (int k = 0; k < SHARD_K_COUNT; ++k) {
         for (size_t i = 0; i + 1 < t.used[k]; i += 2) {
             float ms = 0.f;

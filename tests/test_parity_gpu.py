@@ -279,3 +279,45 @@ def test_seeded_shape_sweep_two_prefill_chunks_then_decode(lib, case):
     want = H.run_oracle(cfg, layers, chunks)
     H.assert_parity(got, want, H.TOL[c["dtype"]], str(c))
     sh.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_micro_batches_on_several_streams(lib, dtype):
+    """Six sequences driven like pipeline micro-batches: prefills on one stream, then decode
+    steps round-robin over five streams - one more than the shard has workspace sets, so a
+    set changes hands (the library orders that with events) - while a late prefill of a
+    seventh sequence runs next to them.  Every output against the oracle."""
+    torch = H.torch_mod()
+    cfg = synth.model_cfg("tiny", d_model=256, n_heads=4, n_kv_heads=2, head_dim=64, ffn_dim=688)
+    n_seq, T, n_dec, seed = 6, 40, 5, 31
+    layers = H.make_layers(cfg, seed, 2, dtype, gains=True)
+    sh = H.gpu_shard(lib, cfg, layers, dtype, max_seqs=n_seq + 1, max_seq_len=T + n_dec, page_size=16, max_batch_tokens=T)
+    ids = [sh.seq_alloc() for _ in range(n_seq + 1)]
+    main = torch.cuda.current_stream()
+    streams = [torch.cuda.Stream() for _ in range(5)]
+    xp = [H.to_dev(synth.hidden_states(cfg, seed, "prefill", 0, b, 1, T)) for b in range(n_seq + 1)]
+    xd = [[H.to_dev(synth.hidden_states(cfg, seed, "dec", s, b, 1, 1)) for b in range(n_seq)] for s in range(n_dec)]
+    yp = [torch.empty_like(x) for x in xp]
+    yd = [[torch.empty_like(x) for x in row] for row in xd]
+    for b in range(n_seq):
+        sh.prefill([ids[b]], T, xp[b], yp[b], main.cuda_stream)
+    for q in streams:
+        q.wait_stream(main)
+    for s in range(n_dec):
+        for b in range(n_seq):
+            q = streams[(b + s) % len(streams)]
+            if s > 0:                       # this sequence's previous step ran on another stream
+                q.wait_stream(streams[(b + s - 1) % len(streams)])
+            sh.decode([ids[b]], xd[s][b], yd[s][b], q.cuda_stream)
+        if s == 1:                           # a prefill in the middle of the decode traffic
+            sh.prefill([ids[n_seq]], T, xp[n_seq], yp[n_seq], main.cuda_stream)
+    torch.cuda.synchronize()
+    o = H.orc.OracleShard(cfg, layers)
+    for b in range(n_seq + 1):
+        want = o.forward(b, xp[b].cpu().numpy()[0].astype(np.float64))
+        assert H.orc.max_rel_err(yp[b].cpu().numpy()[0], want) <= H.TOL[dtype], f"prefill of sequence {b}"
+    for s in range(n_dec):
+        for b in range(n_seq):
+            want = o.forward(b, xd[s][b].cpu().numpy()[0].astype(np.float64))
+            assert H.orc.max_rel_err(yd[s][b].cpu().numpy()[0], want) <= H.TOL[dtype], f"step {s} of sequence {b}"
+    sh.close()
