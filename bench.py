@@ -141,16 +141,21 @@ def main():
     st = stream.cuda_stream
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
-    # micro-batches are independent sequences: their decode steps go round-robin over two
-    # streams, so that one micro-batch's kernels fill the ramp and tail of the other's
+    # micro-batches are independent sequences: their calls go round-robin over two streams, so
+    # that one micro-batch's kernels fill the ramp and tail of the other's
     side = [torch.cuda.Stream() for _ in range(min(MB, 2))] if MB > 1 else []
 
     def one_step(timed):
         ids = [[sh.seq_alloc() for _ in range(B)] for _ in range(MB)]
         e0, e1, e2 = ev(), ev(), ev()
         e0.record(stream)
+        for q in side:
+            q.wait_stream(stream)
         for mb in range(MB):
-            sh.prefill(ids[mb], T, x_pre[mb], y_pre[mb], st)
+            q = side[mb % len(side)].cuda_stream if side else st
+            sh.prefill(ids[mb], T, x_pre[mb], y_pre[mb], q)
+        for q in side:
+            stream.wait_stream(q)
         e1.record(stream)
         for q in side:
             q.wait_stream(stream)

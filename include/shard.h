@@ -28,10 +28,10 @@
  *  - A shard handle is not thread-safe; use one thread per handle at a time.
  *  - Several streams: calls issued (from that one thread) on different streams may overlap on
  *    the device when they carry different sequences - micro-batches of a pipeline stage, for
- *    instance.  The shard keeps SHARD_MAX_STREAMS workspace sets (one large enough for
- *    prefill) and orders its own reuse of them with events, so any pattern of streams is
- *    safe; up to SHARD_MAX_STREAMS decode streams, or one prefill next to decode streams, run
- *    without waiting for each other.  The caller orders calls that touch the SAME sequence
+ *    instance.  The shard keeps SHARD_MAX_STREAMS workspace sets (all of them large enough for
+ *    a prefill of max_batch_tokens when such a set is below 256 MB, otherwise only one) and
+ *    orders its own reuse of them with events, so any pattern of streams is safe; up to
+ *    SHARD_MAX_STREAMS streams run without waiting for each other.  The caller orders calls that touch the SAME sequence
  *    (its decode after its prefill, step after step), as on a single stream.
  */
 #ifndef SHARD_H

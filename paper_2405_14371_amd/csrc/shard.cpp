@@ -88,6 +88,7 @@ struct shard {
         void* f = nullptr;     // [rows, F]      SwiGLU output   (same)
         float* part_o = nullptr;
         float* part_ml = nullptr;
+        size_t rows = 0;       // activation rows the set can hold
         hipStream_t owner = nullptr;
         bool used = false;
         uint64_t last_use = 0;
@@ -428,26 +429,21 @@ void run_decode(shard* s, shard::Work& wk, const SeqBatch& sb, const float* x_in
     }
 }
 
-// The workspace set a call on stream `st` uses.  Prefill always takes set 0 (the only one with
-// mmax rows); decode prefers a set the stream already owns, then a free small set, then set 0,
-// then the least recently used one.  Taking over another stream's set first makes `st` wait
-// for that stream's last use of it.
-int acquire_work(shard* s, hipStream_t st, bool prefill, shard::Work** out) {
+// The workspace set a call with `rows` activation rows on stream `st` uses: a set the stream
+// already owns, else a free one (small sets first for small calls, so that the large ones stay
+// available to prefill), else the least recently used one that is large enough.  Taking over
+// another stream's set first makes `st` wait for that stream's last use of it.
+int acquire_work(shard* s, hipStream_t st, size_t rows, shard::Work** out) {
     shard::Work* w = nullptr;
-    if (prefill) {
-        w = &s->work[0];
-    } else {
+    for (auto& c : s->work)
+        if (c.used && c.owner == st && c.rows >= rows) { w = &c; break; }
+    for (int i = SHARD_MAX_STREAMS - 1; !w && i >= 0; --i)   // sets are sized large first: search from the back
+        if (!s->work[i].used && s->work[i].rows >= rows) w = &s->work[i];
+    if (!w) {
         for (auto& c : s->work)
-            if (c.used && c.owner == st) { w = &c; break; }
-        for (int i = 1; !w && i < SHARD_MAX_STREAMS; ++i)
-            if (!s->work[i].used) w = &s->work[i];
-        if (!w && !s->work[0].used) w = &s->work[0];
-        if (!w) {
-            w = &s->work[0];
-            for (auto& c : s->work)
-                if (c.last_use < w->last_use) w = &c;
-        }
+            if (c.rows >= rows && (!w || c.last_use < w->last_use)) w = &c;
     }
+    if (!w) return fail(SHARD_E_INVAL, "no workspace holds %zu rows", rows);  // cannot happen: set 0 holds mmax
     if (w->used && w->owner != st) HIP_TRY(hipStreamWaitEvent(st, w->done, 0));
     w->owner = st;
     w->used = true;
@@ -579,7 +575,11 @@ int shard_create(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg
     const size_t units = static_cast<size_t>(SHARD_MAX_BATCH) * model->n_heads;
     for (int wi = 0; wi < SHARD_MAX_STREAMS; ++wi) {
         shard::Work& w = s->work[wi];
-        const size_t rows = wi == 0 ? static_cast<size_t>(s->mmax) : static_cast<size_t>(SHARD_MAX_BATCH);
+        // every set takes a whole prefill when that is cheap (256 MB); otherwise only set 0 does
+        const size_t row_bytes = static_cast<size_t>(d) * es + 2ull * s->nq * sizeof(float) + static_cast<size_t>(F) * sizeof(float);
+        const bool big = wi == 0 || static_cast<size_t>(s->mmax) * row_bytes <= (256ull << 20);
+        const size_t rows = big ? static_cast<size_t>(s->mmax) : static_cast<size_t>(SHARD_MAX_BATCH);
+        w.rows = rows;
         CREATE_TRY(hipMalloc(&w.h, rows * d * es));
         CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&w.q), rows * s->nq * sizeof(float)));
         CREATE_TRY(hipMalloc(&w.o, rows * s->nq * sizeof(float)));
@@ -654,7 +654,7 @@ int shard_prefill(shard_t* s, const int32_t* seq_ids, int32_t B, int32_t T, cons
     if (!x_in || !x_out) return fail(SHARD_E_INVAL, "null activation pointer");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     shard::Work* wk = nullptr;
-    rc = acquire_work(s, st, true, &wk);
+    rc = acquire_work(s, st, static_cast<size_t>(B) * T, &wk);
     if (rc) return rc;
     grow_sequences(s, sb, T, st);
     run_prefill(s, *wk, sb, T, static_cast<const float*>(x_in), static_cast<float*>(x_out), st);
@@ -670,7 +670,7 @@ int shard_decode(shard_t* s, const int32_t* seq_ids, int32_t B, const void* x_in
     if (!x_in || !x_out) return fail(SHARD_E_INVAL, "null activation pointer");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     shard::Work* wk = nullptr;
-    rc = acquire_work(s, st, false, &wk);
+    rc = acquire_work(s, st, static_cast<size_t>(B), &wk);
     if (rc) return rc;
     grow_sequences(s, sb, 1, st);
     run_decode(s, *wk, sb, static_cast<const float*>(x_in), static_cast<float*>(x_out), st);
