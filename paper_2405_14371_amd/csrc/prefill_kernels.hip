@@ -803,7 +803,9 @@ __global__ __launch_bounds__(256 * KS) void prefill_attn_lds_kernel(PrefillAttn 
 
     // this lane's share of a stage: NPER loads, each 16 bytes of one K or V row
     auto swz_k = [](int r) { return CHR >= 16 ? (r & 15) : ((r >> 1) & 7); };
-    auto swz_v = [](int r) { return ((r >> 2) & 1) * (F16 ? 4 : 8); };
+    // V rows: consecutive rows land in different 32-byte slots of the row (eight of them when
+    // the row has 16 chunks, four when it has 8), so that the column reads of V^T spread over banks
+    auto swz_v = [](int r) { return CHR >= 16 ? (r & 7) << 1 : (r & 3) << 1; };
     int ld_row[NPER], ld_chunk[NPER];
     bool ld_isv[NPER];
 #pragma unroll
@@ -928,14 +930,26 @@ __global__ __launch_bounds__(256 * KS) void prefill_attn_lds_kernel(PrefillAttn 
                 for (int i = 0; i < 8; ++i) pf[i] = static_cast<f16_t>(s[mm * 8 + i]);
 #pragma unroll
                 for (int j = 0; j < DH / 32; ++j) {
-                    f16x8_t vf;
+                    // V^T fragment by two transposing LDS reads (ds_read_b64_tr_b16): within
+                    // 16 lanes, lane m hands in the address of 4 halfs of one row and lane
+                    // (g, e) = (m / 4, m % 4) receives element e of the rows of lanes g, g + 4,
+                    // g + 8, g + 12.  Lane m therefore points at key row m / 4 of the group,
+                    // features 4 * (m % 4) .. + 3 of its 16-feature block, and gets the four
+                    // keys of the group for its own feature.
+                    typedef short i16x4_t __attribute__((ext_vector_type(4)));
+                    typedef short i16x8_t __attribute__((ext_vector_type(8)));
+                    i16x8_t vraw;
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const int r = mm * 16 + (i >> 2) * 8 + half * 4 + (i & 3);
-                        const int d = j * 32 + l32;
-                        vf[i] = *reinterpret_cast<const f16_t*>(sV + r * ROWB + (((d >> 3) ^ swz_v(r)) << 4) + (d & 7) * 2);
+                    for (int grp = 0; grp < 2; ++grp) {
+                        const int m16 = lane & 15, dblk = (lane >> 4) & 1;
+                        const int r = mm * 16 + grp * 8 + half * 4 + (m16 >> 2);
+                        const int d = j * 32 + dblk * 16 + 4 * (m16 & 3);
+                        const char* at = sV + r * ROWB + (((d >> 3) ^ swz_v(r)) << 4) + (d & 7) * 2;
+                        const i16x4_t t = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (__attribute__((address_space(3))) i16x4_t*)(at));
+                        vraw[grp * 4 + 0] = t[0]; vraw[grp * 4 + 1] = t[1]; vraw[grp * 4 + 2] = t[2]; vraw[grp * 4 + 3] = t[3];
                     }
-                    o[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf, o[j], 0, 0, 0);
+                    o[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, vraw), pf, o[j], 0, 0, 0);
                 }
             }
         } else {
