@@ -2,7 +2,7 @@
 """Benchmark of the shard forward pass on one MI355X.
 
 One *step* is one pass of the whole hot path over one batch of synthetic input on the
-workload the benchmark's metric is quoted on: a Llama2-7B-shaped shard, layers 0-7 of 32,
+headline workload: a Llama2-7B-shaped shard, layers 0-7 of 32,
 fp32 weights, batch 1, a 512-token prefill followed by 128 decode steps.  Weights and all
 inputs are resident in HBM before the timed region.  Prints one JSON line.
 

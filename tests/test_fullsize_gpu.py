@@ -1,4 +1,4 @@
-"""Full-size parity: the workloads of the benchmark spec at their real sizes, in the launch
+"""Full-size parity: the benchmark workloads at their real sizes, in the launch
 configuration bench.py times, against stored oracle outputs.
 
 The expected values in tests/golden/<name>.npz were written by tests/golden/make_golden.py,

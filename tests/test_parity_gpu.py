@@ -34,7 +34,7 @@ def run_case(lib, cfg, n_layers, dtype, B, T, n_dec, seed=0, gains=False, page_s
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_tiny_config_prefill_32_decode_16(lib, dtype):
-    """BASELINE config 1: 2 layers, d 256, 4 heads x 64, FFN 688, batch 1, 32 + 16."""
+    """The tiny configuration: 2 layers, d 256, 4 heads x 64, FFN 688, batch 1, 32 + 16."""
     run_case(lib, synth.model_cfg("tiny"), 2, dtype, B=1, T=32, n_dec=16)
 
 
