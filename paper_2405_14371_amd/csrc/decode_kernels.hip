@@ -13,12 +13,17 @@ namespace shk {
 // lane are in flight.  Partial sums are reduced across the wave with shuffles, across the
 // four waves through LDS, always in the same order.
 // ---------------------------------------------------------------------------------------
-template <typename WT, int NB, int R, int U>
+template <typename WT, int NB, int R, int U, bool ROT = false>
 __global__ __launch_bounds__(256) void decode_linear_kernel(DecodeLinear a, SeqBatch sb) {
     constexpr int VEC = Elem<WT>::VEC;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int row0 = blockIdx.x * R;
     const int nchunk = a.K / VEC;
+    // ROT: every workgroup starts its walk over K at its own 4 KB iteration.  With long rows
+    // (K = 11008) this spreads the workgroups of a launch over the memory channels (+3..7 %);
+    // with K = 4096 it gains nothing and costs a few instructions, so it is opt-in per shape.
+    const int iters = (nchunk + 255) / 256;
+    const int rot = ROT ? static_cast<int>((blockIdx.x * 5u) % static_cast<unsigned>(iters)) * 256 : 0;
     const WT* __restrict__ W = static_cast<const WT*>(a.W);
     const bool norm = a.gain != nullptr;
 
@@ -51,6 +56,10 @@ __global__ __launch_bounds__(256) void decode_linear_kernel(DecodeLinear a, SeqB
             const int c = c0 + 256 * u;
             ok[u] = c < nchunk;
             cc[u] = ok[u] ? c : c0;
+            if constexpr (ROT) {  // walk K from a per-workgroup offset (a rotation of the chunk index)
+                cc[u] += rot;
+                if (cc[u] >= nchunk) cc[u] -= nchunk;
+            }
 #pragma unroll
             for (int r = 0; r < R; ++r) w[u][r].load_stream(rowp[r] + static_cast<size_t>(cc[u]) * VEC);
         }
@@ -173,10 +182,10 @@ __global__ __launch_bounds__(256) void decode_linear_kernel(DecodeLinear a, SeqB
     }
 }
 
-template <typename WT, int NB, int R, int U>
+template <typename WT, int NB, int R, int U, bool ROT = false>
 static void launch_dl(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
     const int grid = (a.N + R - 1) / R;
-    launch((decode_linear_kernel<WT, NB, R, U>), dim3(grid), dim3(256), 0, st, a, sb);
+    launch((decode_linear_kernel<WT, NB, R, U, ROT>), dim3(grid), dim3(256), 0, st, a, sb);
 }
 
 // (rows per workgroup, chunks in flight) from a sweep on MI355X over the Llama2 shapes:
@@ -187,7 +196,7 @@ static void launch_dl_t(const DecodeLinear& a, const SeqBatch& sb, hipStream_t s
     constexpr bool f32 = sizeof(WT) == 4;
     if (a.nb == 1) {
         if (a.N >= 8192) { if (f32) launch_dl<WT, 1, 4, 1>(a, sb, st); else launch_dl<WT, 1, 8, 1>(a, sb, st); }
-        else if (a.K > 8192) { if (f32) launch_dl<WT, 1, 2, 2>(a, sb, st); else launch_dl<WT, 1, 4, 2>(a, sb, st); }
+        else if (a.K > 8192) { if (f32) launch_dl<WT, 1, 4, 2, true>(a, sb, st); else launch_dl<WT, 1, 4, 2, true>(a, sb, st); }
         else { if (f32) launch_dl<WT, 1, 2, 4>(a, sb, st); else launch_dl<WT, 1, 4, 1>(a, sb, st); }
     }
     else if (a.nb == 2) launch_dl<WT, 2, 4, 2>(a, sb, st);
