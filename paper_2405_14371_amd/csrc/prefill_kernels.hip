@@ -805,7 +805,8 @@ __global__ __launch_bounds__(256 * KS) void prefill_attn_lds_kernel(PrefillAttn 
     auto swz_k = [](int r) { return CHR >= 16 ? (r & 15) : ((r >> 1) & 7); };
     // V rows: consecutive rows land in different 32-byte slots of the row (eight of them when
     // the row has 16 chunks, four when it has 8), so that the column reads of V^T spread over banks
-    auto swz_v = [](int r) { return CHR >= 16 ? (r & 7) << 1 : (r & 3) << 1; };
+    // (fp32 reads V element by element: there only the two half-waves, rows 4 apart, have to differ)
+    auto swz_v = [](int r) { return !F16 ? ((r >> 2) & 1) * 8 : CHR >= 16 ? (r & 7) << 1 : (r & 3) << 1; };
     int ld_row[NPER], ld_chunk[NPER];
     bool ld_isv[NPER];
 #pragma unroll
