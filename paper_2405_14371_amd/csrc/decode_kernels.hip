@@ -249,6 +249,7 @@ __global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLi
     for (int t = 0; t < TILES; ++t)
 #pragma unroll
         for (int v = 0; v < 4; ++v) acc[t][v] = 0.f;
+    float ssq = 0.f;
 
     for (int kb0 = wave; kb0 < nblk; kb0 += WAVES * U) {
         uint4 wv[U][TILES][2], xv[U][2];
@@ -267,26 +268,42 @@ __global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLi
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < 2; ++j) {
+                if (a.norm_xb) {  // sum of squares of this lane's activation row, for the RMSNorm scale
+                    const f16x8_d h = __builtin_bit_cast(f16x8_d, xv[u][j]);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) ssq = fmaf(static_cast<float>(h[e]), static_cast<float>(h[e]), ssq);
+                }
 #pragma unroll
                 for (int t = 0; t < TILES; ++t)
                     acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_d, wv[u][t][j]),
                                                                     __builtin_bit_cast(f16x8_d, xv[u][j]), acc[t], 0, 0, 0);
+            }
     }
 
     // D[n][b]: register v of a lane is row 4*g + v of its tile, activation row l16
     __shared__ float s_red[WAVES][ROWS][16];
     __shared__ float s_val[ROWS][16];
+    __shared__ float s_ssq[WAVES][16];
 #pragma unroll
     for (int t = 0; t < TILES; ++t)
 #pragma unroll
         for (int v = 0; v < 4; ++v) s_red[wave][t * 16 + g * 4 + v][l16] = acc[t][v];
+    ssq += __shfl_xor(ssq, 16, 64);   // the four lanes of an activation row hold different k
+    ssq += __shfl_xor(ssq, 32, 64);
+    if (g == 0) s_ssq[wave][l16] = ssq;
     __syncthreads();
     for (int id = tid; id < ROWS * 16; id += THREADS) {
         const int r = id >> 4, b = id & 15;
         float v = 0.f;
 #pragma unroll
         for (int w = 0; w < WAVES; ++w) v += s_red[w][r][b];
+        if (a.norm_xb) {
+            float q = 0.f;
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) q += s_ssq[w][b];
+            v *= 1.0f / sqrtf(q / static_cast<float>(K) + a.eps);
+        }
         s_val[r][b] = v;
     }
     __syncthreads();
@@ -296,7 +313,9 @@ __global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLi
             const int r = id >> 4, b = id & 15, n = row0 + r;
             if (n < a.N && b < a.nb) {
                 const size_t at = static_cast<size_t>(b) * a.N + n;
-                a.out[at] = a.resid[at] + s_val[r][b];
+                const float y = a.resid[at] + s_val[r][b];
+                a.out[at] = y;
+                if (a.out_h) static_cast<f16_t*>(a.out_h)[at] = static_cast<f16_t>(y);
             }
         }
         return;
@@ -583,6 +602,47 @@ void launch_decode_attn(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st)
 int decode_attn_tokens_per_trip(int kv_dtype, int dh) {
     const int vec = kv_dtype == DT_F32 ? 4 : 8;
     return 4 * 256 / (dh / vec);
+}
+
+// W[n][k] *= gain[k] on a half matrix, 8 elements per thread
+__global__ __launch_bounds__(256) void scale_columns_f16_kernel(f16_t* W, const float* __restrict__ gain, size_t n8, int K,
+                                                               uint32_t* overflow) {
+    const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= n8) return;
+    typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+    h8* p = reinterpret_cast<h8*>(W) + i;
+    h8 w = *p;
+    const int k0 = static_cast<int>((i * 8) % static_cast<size_t>(K));   // K is a multiple of 8
+    bool over = false;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float v = static_cast<float>(w[e]) * gain[k0 + e];
+        over |= fabsf(v) > 65504.0f;
+        w[e] = static_cast<f16_t>(v);
+    }
+    *p = w;
+    if (over) atomicOr(overflow, 1u);
+}
+
+void launch_scale_columns_f16(void* W, const float* gain, int32_t N, int32_t K, uint32_t* overflow, hipStream_t st) {
+    const size_t n8 = static_cast<size_t>(N) * K / 8;
+    launch(scale_columns_f16_kernel, dim3(static_cast<unsigned>((n8 + 255) / 256)), dim3(256), 0, st,
+           static_cast<f16_t*>(W), gain, n8, K, overflow);
+}
+
+__global__ __launch_bounds__(256) void to_half_kernel(const float* __restrict__ x, f16_t* __restrict__ out, size_t n4) {
+    const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= n4) return;
+    const float4 t = reinterpret_cast<const float4*>(x)[i];
+    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+    h4 o;
+    o[0] = static_cast<f16_t>(t.x); o[1] = static_cast<f16_t>(t.y); o[2] = static_cast<f16_t>(t.z); o[3] = static_cast<f16_t>(t.w);
+    reinterpret_cast<h4*>(out)[i] = o;
+}
+
+void launch_to_half(const float* x, void* out, size_t n, hipStream_t st) {
+    const size_t n4 = n / 4;
+    launch(to_half_kernel, dim3(static_cast<unsigned>((n4 + 255) / 256)), dim3(256), 0, st, x, static_cast<f16_t*>(out), n4);
 }
 
 // bf16 -> half, in place, 8 elements per thread

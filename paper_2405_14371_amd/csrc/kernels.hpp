@@ -89,8 +89,11 @@ struct DecodeLinear {
     KvView kv;
     const float2* rope;    // [max_seq_len, dh/2] (cos, sin)
     // matrix-core variant (launch_decode_linear_mfma): half weights, up to 16 rows
-    const void* xb;        // [nb, K] half activations (already normalised where needed)
+    const void* xb;        // [nb, K] half activations
     void* out_b;           // EPI_SWIGLU output [nb, N/2] half
+    int32_t norm_xb;       // non-zero: xb is un-normalised; scale row b of the result by
+                           // rsqrt(mean_k xb[b][k]^2 + eps) (RMSNorm with the gain folded into W)
+    void* out_h;           // EPI_RESID: non-null -> also store the result as half [nb, N]
 };
 void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st);
 // same contract with xb/out_b; requires wt == DT_F16, nb <= 16, K % 64 == 0, gain == null
@@ -146,6 +149,12 @@ struct PrefillAttn {
     KvView kv;
 };
 void launch_prefill_attn(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st);
+
+// W[n][k] *= gain[k] for a half matrix [N, K] (RMSNorm gains folded into the matrix that
+// consumes the normalised vector); *overflow is set when a product leaves half's range.
+void launch_scale_columns_f16(void* W, const float* gain, int32_t N, int32_t K, uint32_t* overflow, hipStream_t st);
+// out[i] = half(x[i]), i < n (n a multiple of 4)
+void launch_to_half(const float* x, void* out, size_t n, hipStream_t st);
 
 // In place: n bf16 values -> n IEEE half values (round to nearest; exact for every bf16 in
 // half's normal range).  *overflow is set when a finite value exceeds half's range.

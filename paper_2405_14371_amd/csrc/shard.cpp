@@ -311,11 +311,18 @@ int pick_nsplit(const shard* s, const SeqBatch& sb) {
 
 // Decode step with 16-bit weights and more than 4 sequences: projections on the matrix
 // cores, one pass over the weights per group of up to 16 sequences (the streaming kernels'
-// vector ALUs fall behind the HBM stream from about 8 rows on).
+// vector ALUs fall behind the HBM stream from about 8 rows on).  No RMSNorm launches: the
+// gains are part of the 16-bit matrices (folded in at create), each residual epilogue also
+// leaves a half copy of its result, and the consuming projection takes the row scale
+// rsqrt(mean x^2 + eps) from the activation fragments it loads anyway.
 void run_decode_mfma(shard* s, shard::Work& wk, const SeqBatch& all, const float* x_in, float* x_out, hipStream_t st) {
     const shard_model_cfg& m = s->m;
     const int d_model = m.d_model;
     mark_layer(s, 0, st);
+    {
+        Bracket t(s, SHARD_K_DECODE_QKV, st);
+        launch_to_half(x_in, wk.h, static_cast<size_t>(all.n) * d_model, st);
+    }
     for (int li = 0; li < s->L; ++li) {
         const LayerDev& l = s->layers[li];
         const KvView kvv = kv_view(s, li);
@@ -326,12 +333,12 @@ void run_decode_mfma(shard* s, shard::Work& wk, const SeqBatch& all, const float
             const int B = sb.n;
             const float* x = (li == 0 ? x_in : x_out) + static_cast<size_t>(b0) * d_model;
             float* y = x_out + static_cast<size_t>(b0) * d_model;
+            void* xh = static_cast<char*>(wk.h) + static_cast<size_t>(b0) * d_model * 2;   // half copy of the residual stream
             DecodeLinear d{};
-            d.wt = DT_F16; d.nb = B; d.hq = m.n_heads; d.kv = kvv; d.rope = s->rope;
+            d.wt = DT_F16; d.nb = B; d.hq = m.n_heads; d.kv = kvv; d.rope = s->rope; d.eps = m.rms_eps;
             {
                 Bracket t(s, SHARD_K_DECODE_QKV, st);
-                launch_rmsnorm(x, l.g_attn, m.rms_eps, wk.h, DT_F16, B, d_model, st);
-                d.W = l.wqkv; d.N = s->nqkv; d.K = d_model; d.xb = wk.h; d.epi = EPI_QKV; d.q = wk.q;
+                d.W = l.wqkv; d.N = s->nqkv; d.K = d_model; d.xb = xh; d.norm_xb = 1; d.epi = EPI_QKV; d.q = wk.q;
                 launch_decode_linear_mfma(d, sb, st);
             }
             {
@@ -342,18 +349,20 @@ void run_decode_mfma(shard* s, shard::Work& wk, const SeqBatch& all, const float
                 launch_decode_attn(a, sb, st);
             }
             {
-                d.W = l.wo; d.N = d_model; d.K = s->nq; d.xb = wk.o; d.epi = EPI_RESID; d.resid = x; d.out = y;
+                d.W = l.wo; d.N = d_model; d.K = s->nq; d.xb = wk.o; d.norm_xb = 0; d.epi = EPI_RESID; d.resid = x; d.out = y;
+                d.out_h = xh;
                 Bracket t(s, SHARD_K_DECODE_O, st);
                 launch_decode_linear_mfma(d, sb, st);
             }
             {
                 Bracket t(s, SHARD_K_DECODE_GATEUP, st);
-                launch_rmsnorm(y, l.g_ffn, m.rms_eps, wk.h, DT_F16, B, d_model, st);
-                d.W = l.wgu; d.N = 2 * m.ffn_dim; d.K = d_model; d.xb = wk.h; d.epi = EPI_SWIGLU; d.out_b = wk.f;
+                d.W = l.wgu; d.N = 2 * m.ffn_dim; d.K = d_model; d.xb = xh; d.norm_xb = 1; d.epi = EPI_SWIGLU; d.out_b = wk.f;
+                d.out_h = nullptr;
                 launch_decode_linear_mfma(d, sb, st);
             }
             {
-                d.W = l.wd; d.N = d_model; d.K = m.ffn_dim; d.xb = wk.f; d.epi = EPI_RESID; d.resid = y; d.out = y;
+                d.W = l.wd; d.N = d_model; d.K = m.ffn_dim; d.xb = wk.f; d.norm_xb = 0; d.epi = EPI_RESID; d.resid = y; d.out = y;
+                d.out_h = li + 1 < s->L ? xh : nullptr;
                 Bracket t(s, SHARD_K_DECODE_DOWN, st);
                 launch_decode_linear_mfma(d, sb, st);
             }
@@ -545,6 +554,16 @@ int shard_create(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg
         }
         CREATE_TRY(hipMemcpy(l.g_attn, w[i].g_attn, d * sizeof(float), kind));
         CREATE_TRY(hipMemcpy(l.g_ffn, w[i].g_ffn, d * sizeof(float), kind));
+        if (model->weight_dtype == SHARD_BF16) {
+            // W (g * x_hat) = (W diag g) x_hat: the RMSNorm gains become part of the half matrices
+            // that consume the normalised vector, and the gains the kernels still multiply by are 1
+            launch_scale_columns_f16(l.wqkv, l.g_attn, s->nqkv, d, cvt_flag, nullptr);
+            launch_scale_columns_f16(l.wgu, l.g_ffn, 2 * F, d, cvt_flag, nullptr);
+            CREATE_TRY(hipDeviceSynchronize());
+            const std::vector<float> ones(d, 1.0f);
+            CREATE_TRY(hipMemcpy(l.g_attn, ones.data(), d * sizeof(float), hipMemcpyHostToDevice));
+            CREATE_TRY(hipMemcpy(l.g_ffn, ones.data(), d * sizeof(float), hipMemcpyHostToDevice));
+        }
         // a cache that was never written must still hold finite numbers (masked lanes read it)
         CREATE_TRY(hipMemset(l.k, 0, page_elems * s->n_pages * es));
         CREATE_TRY(hipMemset(l.v, 0, page_elems * s->n_pages * es));
@@ -600,7 +619,7 @@ int shard_create(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg
         if (e1 != hipSuccess || over) {
             free_all(s);
             return e1 != hipSuccess ? fail(SHARD_E_HIP, "reading the conversion flag: %s", hipGetErrorString(e1))
-                                    : fail(SHARD_E_INVAL, "a bf16 weight exceeds the range of IEEE half (65504)");
+                                    : fail(SHARD_E_INVAL, "a bf16 weight (times its RMSNorm gain, for wq/wk/wv/w_gate/w_up) exceeds the range of IEEE half (65504)");
         }
     }
 #undef CREATE_TRY
@@ -857,7 +876,7 @@ int shard_ends_create(shard_ends_t** out, const shard_model_cfg* model, int32_t 
 #undef ENDS_TRY
     if (over) {
         free_ends(e);
-        return fail(SHARD_E_INVAL, "a bf16 weight exceeds the range of IEEE half (65504)");
+        return fail(SHARD_E_INVAL, "a bf16 weight (times its RMSNorm gain, for wq/wk/wv/w_gate/w_up) exceeds the range of IEEE half (65504)");
     }
     *out = e;
     return SHARD_OK;
