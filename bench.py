@@ -209,7 +209,7 @@ def main():
             traffic = json.load(fh)[args.workload]["decode_linear_kernel"]["traffic_bytes_per_launch"]
     except (OSError, KeyError, ValueError):
         pass
-    n_lin = 4 * calls_dec                   # projection launches (the batched path's RMSNorm launches not counted)
+    n_lin = 4 * calls_dec                   # projection launches (the batched path's one cast of x_in per step not counted)
     roofline = {
         "kernel": ("decode_linear_mfma_kernel" if mfma_decode else "decode_linear_kernel")
                   + " (weight-streaming projections of shard_decode)",

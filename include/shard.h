@@ -75,7 +75,10 @@ typedef struct {
                              (same 2 bytes per element; every bf16 value of magnitude 6.1e-5 ..
                              65504 converts exactly, smaller ones round onto half's subnormal grid,
                              absolute error <= 3e-8; a larger one makes shard_create fail with
-                             SHARD_E_INVAL).  The KV cache and the activations fed to the matrix
+                             SHARD_E_INVAL).  The RMSNorm gains are multiplied into the converted
+                             wq/wk/wv/w_gate/w_up (W (g * x_hat) = (W diag g) x_hat; one more
+                             rounding to half per weight, and the product must stay within
+                             65504 too).  The KV cache and the activations fed to the matrix
                              cores are half as well (8x finer rounding than bf16); accumulation and
                              the residual stream are fp32. */
     int32_t act_dtype;    /* dtype of x_in / x_out at the boundary; only SHARD_F32 is supported:
@@ -169,7 +172,7 @@ int shard_profile(shard_t *s, int32_t B, int32_t T_prefill, int32_t n_decode, in
  * far and returns kernel launches and total kernel seconds per class since enable.  The
  * classes are the steps of the layer, separately for the autoregressive and the prefill
  * phase; a class may hold more than one kernel per layer (attention + its merge; the
- * RMSNorm of the batched half-precision decode path counts with the projection it feeds). */
+ * one-off cast of x_in to half on the batched 16-bit decode path counts with the QKV class). */
 enum {
     SHARD_K_DECODE_QKV = 0,     /* RMSNorm + QKV projection + RoPE + KV append */
     SHARD_K_DECODE_ATTN = 1,
