@@ -219,7 +219,8 @@ void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t
 // 64-element blocks, U of them in flight per wave, and meet in LDS (fixed order).  Lane
 // (row = lane%16, g = lane/16) supplies elements 32*j + 8*g + (0..7) of a block to MFMA j on
 // both operands, so every load instruction reads 64 contiguous bytes per row.  Activations
-// arrive already rounded to half (and normalised where the step needs it).
+// arrive rounded to half; with norm_xb they are the un-normalised residual stream, and the
+// RMSNorm row scale (gains folded into W) comes from the fragments loaded for the MFMAs.
 // ---------------------------------------------------------------------------------------
 typedef _Float16 f16x8_d __attribute__((ext_vector_type(8)));
 typedef float f32x4_d __attribute__((ext_vector_type(4)));
@@ -320,47 +321,49 @@ __global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLi
         }
         return;
     }
-    // pair epilogues: thread -> (row pair j, activation row b)
-    static_assert(THREADS >= ROWS * 8, "one thread per (row pair, activation row)");
-    if (tid >= ROWS * 8) return;   // ROWS/2 row pairs x 16 activation rows
-    const int j = tid >> 4, b = tid & 15;
-    const int n0 = row0 + 2 * j;
-    if (n0 >= a.N || b >= a.nb) return;
-    const float v0 = s_val[2 * j][b], v1 = s_val[2 * j + 1][b];
-    if (a.epi == EPI_SWIGLU) {
-        const int F = a.N / 2;
-        static_cast<f16_t*>(a.out_b)[static_cast<size_t>(b) * F + n0 / 2] = static_cast<f16_t>(v0 / (1.0f + expf(-v0)) * v1);
-        return;
-    }
-    const int dh = a.kv.dh, nq = a.hq * dh, nk = a.kv.hkv * dh;
-    const int pos = sb.pos[b];
-    const int e = n0 % dh;
-    if (n0 < nq + nk) {
-        const float2 cs = a.rope[static_cast<size_t>(pos) * (dh / 2) + e / 2];
-        const float r0 = v0 * cs.x - v1 * cs.y, r1 = v0 * cs.y + v1 * cs.x;
-        if (n0 < nq) {
-            a.q[static_cast<size_t>(b) * nq + n0] = r0;
-            a.q[static_cast<size_t>(b) * nq + n0 + 1] = r1;
-            return;
+    // pair epilogues: one (row pair j, activation row b) per thread and trip
+    for (int id = tid; id < ROWS * 8; id += THREADS) {   // ROWS/2 row pairs x 16 activation rows
+        const int j = id >> 4, b = id & 15;
+        const int n0 = row0 + 2 * j;
+        if (n0 >= a.N || b >= a.nb) continue;
+        const float v0 = s_val[2 * j][b], v1 = s_val[2 * j + 1][b];
+        if (a.epi == EPI_SWIGLU) {
+            const int F = a.N / 2;
+            static_cast<f16_t*>(a.out_b)[static_cast<size_t>(b) * F + n0 / 2] = static_cast<f16_t>(v0 / (1.0f + expf(-v0)) * v1);
+            continue;
         }
-        const int hk = (n0 - nq) / dh;
+        const int dh = a.kv.dh, nq = a.hq * dh, nk = a.kv.hkv * dh;
+        const int pos = sb.pos[b];
+        const int e = n0 % dh;
+        if (n0 < nq + nk) {
+            const float2 cs = a.rope[static_cast<size_t>(pos) * (dh / 2) + e / 2];
+            const float r0 = v0 * cs.x - v1 * cs.y, r1 = v0 * cs.y + v1 * cs.x;
+            if (n0 < nq) {
+                a.q[static_cast<size_t>(b) * nq + n0] = r0;
+                a.q[static_cast<size_t>(b) * nq + n0 + 1] = r1;
+                continue;
+            }
+            const int hk = (n0 - nq) / dh;
+            const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
+            f16_t* kp = static_cast<f16_t*>(a.kv.k);
+            kp[at] = static_cast<f16_t>(r0);
+            kp[at + 1] = static_cast<f16_t>(r1);
+            continue;
+        }
+        const int hk = (n0 - nq - nk) / dh;
         const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
-        f16_t* kp = static_cast<f16_t*>(a.kv.k);
-        kp[at] = static_cast<f16_t>(r0);
-        kp[at + 1] = static_cast<f16_t>(r1);
-        return;
+        f16_t* vp = static_cast<f16_t*>(a.kv.v);
+        vp[at] = static_cast<f16_t>(v0);
+        vp[at + 1] = static_cast<f16_t>(v1);
     }
-    const int hk = (n0 - nq - nk) / dh;
-    const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
-    f16_t* vp = static_cast<f16_t*>(a.kv.v);
-    vp[at] = static_cast<f16_t>(v0);
-    vp[at + 1] = static_cast<f16_t>(v1);
 }
 
 void launch_decode_linear_mfma(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
     // (row tiles per workgroup, waves splitting K) from a sweep on the 70B shapes: more row
     // tiles re-use each activation fragment, but the launch has to cover 256 compute units
-    if (a.N >= 10240)
+    if (a.N >= 49152)   // enough rows for 128 per workgroup: each activation fragment feeds 8 row tiles
+        launch((decode_linear_mfma_kernel<8, 1, 16>), dim3((a.N + 127) / 128), dim3(1024), 0, st, a, sb);
+    else if (a.N >= 10240)
         launch((decode_linear_mfma_kernel<4, 2, 8>), dim3((a.N + 63) / 64), dim3(512), 0, st, a, sb);
     else
         launch((decode_linear_mfma_kernel<2, 2, 4>), dim3((a.N + 31) / 32), dim3(256), 0, st, a, sb);
