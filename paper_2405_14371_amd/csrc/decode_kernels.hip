@@ -226,12 +226,15 @@ typedef _Float16 f16x8_d __attribute__((ext_vector_type(8)));
 typedef float f32x4_d __attribute__((ext_vector_type(4)));
 
 template <int TILES, int U, int WAVES>
-__global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLinear a, SeqBatch sb) {
+__global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLinear a, SeqBatch sb, int rows_wg) {
     constexpr int ROWS = 16 * TILES;
     constexpr int THREADS = 64 * WAVES;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, g = lane >> 4;
-    const int row0 = blockIdx.x * ROWS;
+    // rows_wg <= ROWS rows per workgroup (even): the launch picks it so that the workgroups
+    // come out as a whole number of rounds over the compute units
+    const int row0 = blockIdx.x * rows_wg;
+    const int row_end = min(row0 + rows_wg, a.N);
     const f16_t* __restrict__ W = static_cast<const f16_t*>(a.W);
     const f16_t* __restrict__ X = static_cast<const f16_t*>(a.xb);
     const int K = a.K, nblk = K / 64;  // K is a multiple of 64 on this path
@@ -242,7 +245,8 @@ __global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLi
 
     const f16_t* wp[TILES];
 #pragma unroll
-    for (int t = 0; t < TILES; ++t) wp[t] = W + static_cast<size_t>(min(row0 + t * 16 + l16, a.N - 1)) * K + g * 8;
+    for (int t = 0; t < TILES; ++t)   // lanes past the workgroup's rows re-read its last row (a cache hit; never stored)
+        wp[t] = W + static_cast<size_t>(min(row0 + t * 16 + l16, row_end - 1)) * K + g * 8;
     const f16_t* xp = X + static_cast<size_t>(l16 < a.nb ? l16 : 0) * K + g * 8;
 
     f32x4_d acc[TILES];
@@ -312,7 +316,7 @@ __global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLi
     if (a.epi == EPI_RESID) {
         for (int id = tid; id < ROWS * 16; id += THREADS) {
             const int r = id >> 4, b = id & 15, n = row0 + r;
-            if (n < a.N && b < a.nb) {
+            if (n < row_end && b < a.nb) {
                 const size_t at = static_cast<size_t>(b) * a.N + n;
                 const float y = a.resid[at] + s_val[r][b];
                 a.out[at] = y;
@@ -325,7 +329,7 @@ __global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLi
     for (int id = tid; id < ROWS * 8; id += THREADS) {   // ROWS/2 row pairs x 16 activation rows
         const int j = id >> 4, b = id & 15;
         const int n0 = row0 + 2 * j;
-        if (n0 >= a.N || b >= a.nb) continue;
+        if (n0 >= row_end || b >= a.nb) continue;
         const float v0 = s_val[2 * j][b], v1 = s_val[2 * j + 1][b];
         if (a.epi == EPI_SWIGLU) {
             const int F = a.N / 2;
@@ -359,14 +363,26 @@ __global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLi
 }
 
 void launch_decode_linear_mfma(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
-    // (row tiles per workgroup, waves splitting K) from a sweep on the 70B shapes: more row
-    // tiles re-use each activation fragment, but the launch has to cover 256 compute units
-    if (a.N >= 49152)   // enough rows for 128 per workgroup: each activation fragment feeds 8 row tiles
-        launch((decode_linear_mfma_kernel<8, 1, 16>), dim3((a.N + 127) / 128), dim3(1024), 0, st, a, sb);
-    else if (a.N >= 10240)
-        launch((decode_linear_mfma_kernel<4, 2, 8>), dim3((a.N + 63) / 64), dim3(512), 0, st, a, sb);
-    else
-        launch((decode_linear_mfma_kernel<2, 2, 4>), dim3((a.N + 31) / 32), dim3(256), 0, st, a, sb);
+    // Rows per workgroup: the workgroups of a launch should come out as whole rounds over the
+    // 256 compute units (a launch of 160 or 448 workgroups leaves units idle for a good part of
+    // it: 70B-shape QKV 44 -> 31 us), with as many rows per workgroup as fit (each activation
+    // fragment then feeds more row tiles), up to 128.
+    constexpr int CUS = 256;
+    const int rounds = ((a.N + CUS - 1) / CUS + 127) / 128;
+    int rows = (a.N + CUS * rounds - 1) / (CUS * rounds);
+    rows += rows & 1;   // the pair epilogues need even row offsets
+    if (rows < 16) rows = 16;
+    const dim3 grid((a.N + rows - 1) / rows);
+    switch ((rows + 15) / 16) {   // one K block in flight per wave; 8 waves split K, 16 for tall workgroups
+        case 1: launch((decode_linear_mfma_kernel<1, 1, 8>), grid, dim3(512), 0, st, a, sb, rows); break;
+        case 2: launch((decode_linear_mfma_kernel<2, 1, 8>), grid, dim3(512), 0, st, a, sb, rows); break;
+        case 3: launch((decode_linear_mfma_kernel<3, 1, 8>), grid, dim3(512), 0, st, a, sb, rows); break;
+        case 4: launch((decode_linear_mfma_kernel<4, 1, 8>), grid, dim3(512), 0, st, a, sb, rows); break;
+        case 5: launch((decode_linear_mfma_kernel<5, 1, 16>), grid, dim3(1024), 0, st, a, sb, rows); break;
+        case 6: launch((decode_linear_mfma_kernel<6, 1, 16>), grid, dim3(1024), 0, st, a, sb, rows); break;
+        case 7: launch((decode_linear_mfma_kernel<7, 1, 16>), grid, dim3(1024), 0, st, a, sb, rows); break;
+        default: launch((decode_linear_mfma_kernel<8, 1, 16>), grid, dim3(1024), 0, st, a, sb, rows); break;
+    }
 }
 
 // ---------------------------------------------------------------------------------------

@@ -69,6 +69,15 @@ def test_bf16_batches_above_4_decode_on_matrix_cores(lib, B):
     run_case(lib, cfg, 2, "bf16", B=B, T=19, n_dec=4, seed=21, gains=True, page_size=16)
 
 
+@pytest.mark.parametrize("ffn", [2240, 5120, 7424, 8960, 11520, 13440, 15360, 20480])
+def test_matrix_core_decode_rows_per_workgroup(lib, ffn):
+    """The MFMA decode projections give every workgroup N / 256 rows (rounded up to even, at
+    most 128, else two rounds): gate/up widths that come out as 18, 40, 58, 70, 90, 106, 120
+    and 2 x 80 rows, i.e. 2..8 row tiles with and without a partial last tile."""
+    cfg = synth.model_cfg("tiny", d_model=256, n_heads=4, n_kv_heads=2, head_dim=64, ffn_dim=ffn)
+    run_case(lib, cfg, 1, "bf16", B=6, T=8, n_dec=2, seed=33, gains=True)
+
+
 def test_long_context_spans_many_key_tiles_and_splits(lib):
     cfg = synth.model_cfg("tiny")
     run_case(lib, cfg, 1, "f32", B=1, T=300, n_dec=3, seed=9)
