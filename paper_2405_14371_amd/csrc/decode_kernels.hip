@@ -592,18 +592,208 @@ __global__ __launch_bounds__(DH) void decode_attn_merge_kernel(DecodeAttn a) {
     else static_cast<f16_t*>(a.o)[at] = static_cast<f16_t>(ox / s_L);
 }
 
+// ---------------------------------------------------------------------------------------
+// Grouped-query variant for half caches with dh = 128 and 4..16 query heads per KV head
+// (the 70B shape: 8).  The vector-ALU kernel above is bound by its FMAs and lane reductions
+// once several heads share every key; here the G heads of one KV head are the second
+// dimension of v_mfma_f32_16x16x32_f16: S^T[token][head] = K[token][:] . q[head][:], a tile
+// of 16 tokens per wave and trip, with K fragments loaded straight from the cache (lane
+// (token, g) reads 16 bytes at dh offset 32 j + 8 g, like a weight row of the projection
+// kernel).  P.V stays on the vector ALUs, where it needs no transposed V: lane l owns
+// output columns 2l, 2l+1 of every head, loads those two V elements of each token and reads
+// the tile's probabilities [token][head] back from LDS as broadcasts - no cross-lane
+// reduction before the end.  Grid (nsplit, nb * hkv); the 4 waves of a workgroup take
+// tiles in turn and meet in LDS; slices are merged by decode_attn_merge_kernel as above.
+// ---------------------------------------------------------------------------------------
+template <int GH>   // heads computed per KV head: 8 or 16 (heads past hq / hkv are padding)
+__global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeAttn a, SeqBatch sb) {
+    constexpr int DH = 128, WAVES = 4, KJ = DH / 32;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, g = lane >> 4;
+    const int G = a.hq / a.kv.hkv;
+    const int split = blockIdx.x, b = blockIdx.y / a.kv.hkv, hk = blockIdx.y % a.kv.hkv;
+    const int h0 = hk * G;
+    const int seq = sb.seq[b];
+    const int ctx = sb.pos[b] + 1;  // the new token's k,v are already in the cache
+    const int per = (ctx + a.nsplit - 1) / a.nsplit;
+    const int u_begin = split * per, u_end = min(ctx, u_begin + per);
+    const f16_t* __restrict__ kp = static_cast<const f16_t*>(a.kv.k);
+    const f16_t* __restrict__ vp = static_cast<const f16_t*>(a.kv.v);
+    const int32_t* bt = a.kv.block_table + static_cast<size_t>(seq) * a.kv.max_pages;
+
+    constexpr int PG_CAP = 512;
+    __shared__ int32_t s_pg[PG_CAP];
+    const int pg_lo = u_begin < u_end ? u_begin / a.kv.page : 0;
+    const int pg_n = u_begin < u_end ? (u_end - 1) / a.kv.page - pg_lo + 1 : 0;
+    const bool pg_cached = pg_n <= PG_CAP;
+    if (pg_cached)
+        for (int i = tid; i < pg_n; i += 256) s_pg[i] = bt[pg_lo + i];
+    __syncthreads();
+
+    // q of head l16, scaled by 1/sqrt(dh) in fp32 and rounded to half once
+    f16x8_d qf[KJ];
+    {
+        const float scale = 1.0f / sqrtf(static_cast<float>(DH));
+        const float* qp = a.q + (static_cast<size_t>(b) * a.hq + h0 + (l16 < G ? l16 : 0)) * DH + 8 * g;
+#pragma unroll
+        for (int j = 0; j < KJ; ++j)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qf[j][e] = l16 < G ? static_cast<f16_t>(qp[32 * j + e] * scale) : static_cast<f16_t>(0.f);
+    }
+
+    float m = -INFINITY, lsum = 0.f;   // of head l16 (lsum: this lane's tokens only until the end)
+    float o[GH][2];
+#pragma unroll
+    for (int h = 0; h < GH; ++h) o[h][0] = o[h][1] = 0.f;
+    __shared__ __align__(16) float s_p[WAVES][16][GH];   // the wave's current tile: exp(s - max) as [token][head]
+    __shared__ __align__(16) float s_c[WAVES][GH];       // rescale factor of the running sums per head
+
+    uint4 ka[KJ], kb[KJ];               // two register sets, used alternately
+    uint32_t va[16], vb[16];
+    auto fetch = [&](int t0, uint4 (&kr)[KJ], uint32_t (&vr)[16]) {
+        const int u = min(t0 + l16, u_end - 1);   // past the slice: re-read its last token, masked below
+        const int pg = u / a.kv.page, slot = u - pg * a.kv.page;
+        const int page_id = pg_cached ? s_pg[pg - pg_lo] : bt[pg];
+        const size_t at = ((static_cast<size_t>(page_id) * a.kv.hkv + hk) * a.kv.page + slot) * DH;
+#pragma unroll
+        for (int j = 0; j < KJ; ++j) kr[j] = *reinterpret_cast<const uint4*>(kp + at + 32 * j + 8 * g);
+        const int lo = static_cast<int>(static_cast<uint32_t>(at)), hi = static_cast<int>(static_cast<uint32_t>(at >> 32));
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {   // lane t holds the row of token t0 + t
+            const size_t att = (static_cast<size_t>(static_cast<uint32_t>(__builtin_amdgcn_readlane(hi, t))) << 32) |
+                               static_cast<uint32_t>(__builtin_amdgcn_readlane(lo, t));
+            vr[t] = *reinterpret_cast<const uint32_t*>(vp + att + 2 * lane);
+        }
+    };
+    auto work = [&](int t0, const uint4 (&kr)[KJ], const uint32_t (&vr)[16]) {
+        f32x4_d acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < KJ; ++j)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_d, kr[j]), qf[j], acc, 0, 0, 0);
+        // register v of lane (head l16, g) is token t0 + 4 g + v
+        float sv[4], mx = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            sv[v] = t0 + 4 * g + v < u_end ? acc[v] : -INFINITY;
+            mx = fmaxf(mx, sv[v]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));   // finite: the tile holds at least one token of the slice
+        const float mn = fmaxf(m, mx);
+        const float corr = __expf(m - mn);        // first tile: exp(-inf) = 0
+        float ps = 0.f;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const float p = __expf(sv[v] - mn);
+            ps += p;
+            if (l16 < GH) s_p[wave][4 * g + v][l16] = p;
+        }
+        lsum = fmaf(lsum, corr, ps);
+        m = mn;
+        if (g == 0 && l16 < GH) s_c[wave][l16] = corr;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the wave reads back what its other lanes wrote
+        __builtin_amdgcn_wave_barrier();
+        {
+            float c[GH];
+#pragma unroll
+            for (int h4 = 0; h4 < GH / 4; ++h4) {
+                const float4 t = *reinterpret_cast<const float4*>(&s_c[wave][4 * h4]);
+                c[4 * h4] = t.x; c[4 * h4 + 1] = t.y; c[4 * h4 + 2] = t.z; c[4 * h4 + 3] = t.w;
+            }
+#pragma unroll
+            for (int h = 0; h < GH; ++h) { o[h][0] *= c[h]; o[h][1] *= c[h]; }
+        }
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+            const h2 vv = __builtin_bit_cast(h2, vr[t]);
+            const float v0 = static_cast<float>(vv[0]), v1 = static_cast<float>(vv[1]);
+#pragma unroll
+            for (int h4 = 0; h4 < GH / 4; ++h4) {
+                const float4 pr = *reinterpret_cast<const float4*>(&s_p[wave][t][4 * h4]);
+                o[4 * h4][0] = fmaf(pr.x, v0, o[4 * h4][0]);         o[4 * h4][1] = fmaf(pr.x, v1, o[4 * h4][1]);
+                o[4 * h4 + 1][0] = fmaf(pr.y, v0, o[4 * h4 + 1][0]); o[4 * h4 + 1][1] = fmaf(pr.y, v1, o[4 * h4 + 1][1]);
+                o[4 * h4 + 2][0] = fmaf(pr.z, v0, o[4 * h4 + 2][0]); o[4 * h4 + 2][1] = fmaf(pr.z, v1, o[4 * h4 + 2][1]);
+                o[4 * h4 + 3][0] = fmaf(pr.w, v0, o[4 * h4 + 3][0]); o[4 * h4 + 3][1] = fmaf(pr.w, v1, o[4 * h4 + 3][1]);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the next tile overwrites s_p
+        __builtin_amdgcn_wave_barrier();
+    };
+    constexpr int STEP = 16 * WAVES;
+    int t0 = u_begin + 16 * wave;
+    if (t0 < u_end) fetch(t0, ka, va);
+    while (t0 < u_end) {
+        if (t0 + STEP < u_end) fetch(t0 + STEP, kb, vb);
+        work(t0, ka, va);
+        t0 += STEP;
+        if (t0 >= u_end) break;
+        if (t0 + STEP < u_end) fetch(t0 + STEP, ka, va);
+        work(t0, kb, vb);
+        t0 += STEP;
+    }
+
+    __shared__ float s_m[WAVES][GH], s_l[WAVES][GH];
+    __shared__ __align__(8) float s_o[WAVES][GH][DH];
+    lsum += __shfl_xor(lsum, 16, 64);
+    lsum += __shfl_xor(lsum, 32, 64);
+    if (g == 0 && l16 < GH) { s_m[wave][l16] = m; s_l[wave][l16] = lsum; }
+#pragma unroll
+    for (int h = 0; h < GH; ++h) *reinterpret_cast<float2*>(&s_o[wave][h][2 * lane]) = make_float2(o[h][0], o[h][1]);
+    __syncthreads();
+
+    for (int id = tid; id < GH * DH; id += 256) {
+        const int h = id / DH, e = id % DH;
+        if (h >= G) break;
+        float M = -INFINITY, L = 0.f, O = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) M = fmaxf(M, s_m[w][h]);
+        if (M > -INFINITY) {
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) {
+                const float wt = __expf(s_m[w][h] - M);  // waves without a tile: exp(-inf) = 0
+                L = fmaf(s_l[w][h], wt, L);
+                O = fmaf(s_o[w][h][e], wt, O);
+            }
+        }
+        const int bh = b * a.hq + h0 + h;
+        if (a.nsplit == 1) {
+            const size_t at = static_cast<size_t>(bh) * DH + e;
+            if (a.o_dtype == DT_F32) static_cast<float*>(a.o)[at] = O / L;
+            else static_cast<f16_t*>(a.o)[at] = static_cast<f16_t>(O / L);
+            continue;
+        }
+        const size_t pbase = static_cast<size_t>(bh) * a.nsplit;
+        a.part_o[(pbase + split) * DH + e] = O;
+        if (e == 0) {
+            a.part_ml[(pbase + split) * 2] = M;
+            a.part_ml[(pbase + split) * 2 + 1] = L;
+        }
+    }
+}
+
+// Whether the grouped-query matrix-core kernel takes a shape.
+static bool decode_attn_gqa(int kv_dtype, int dh, int hq, int hkv) {
+    const int G = hq / hkv;
+    return kv_dtype == DT_F16 && dh == 128 && G >= 4 && G <= 16;
+}
+
 // Query heads handled per workgroup: consecutive heads that share a KV head read its keys
 // and values once (grouped-query attention).
-int decode_attn_heads_per_group(int hq, int hkv) {
+int decode_attn_heads_per_group(int kv_dtype, int dh, int hq, int hkv) {
     const int G = hq / hkv;
+    if (decode_attn_gqa(kv_dtype, dh, hq, hkv)) return G;
     return G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1);
 }
 
 template <typename KT, int DH>
 static void launch_da(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st) {
-    const int gq = decode_attn_heads_per_group(a.hq, a.kv.hkv);
+    const int gq = decode_attn_heads_per_group(a.kv_dtype, DH, a.hq, a.kv.hkv);
     const dim3 grid(a.nsplit, a.nb * a.hq / gq), block(256);
-    if (gq == 4) launch((decode_attn_kernel<KT, DH, 4, 4>), grid, block, 0, st, a, sb);
+    if (decode_attn_gqa(a.kv_dtype, DH, a.hq, a.kv.hkv)) {
+        if (gq <= 8) launch(decode_attn_gqa_kernel<8>, grid, block, 0, st, a, sb);
+        else launch(decode_attn_gqa_kernel<16>, grid, block, 0, st, a, sb);
+    }
+    else if (gq == 4) launch((decode_attn_kernel<KT, DH, 4, 4>), grid, block, 0, st, a, sb);
     else if (gq == 2) launch((decode_attn_kernel<KT, DH, 4, 2>), grid, block, 0, st, a, sb);
     else launch((decode_attn_kernel<KT, DH, 4, 1>), grid, block, 0, st, a, sb);
     if (a.nsplit > 1) launch(decode_attn_merge_kernel<DH>, dim3(a.nb * a.hq), dim3(DH), 0, st, a);
@@ -618,7 +808,8 @@ void launch_decode_attn(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st)
     }
 }
 
-int decode_attn_tokens_per_trip(int kv_dtype, int dh) {
+int decode_attn_tokens_per_trip(int kv_dtype, int dh, int hq, int hkv) {
+    if (decode_attn_gqa(kv_dtype, dh, hq, hkv)) return 64;   // 4 waves x one 16-token tile
     const int vec = kv_dtype == DT_F32 ? 4 : 8;
     return 4 * 256 / (dh / vec);
 }

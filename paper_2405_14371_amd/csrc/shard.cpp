@@ -300,8 +300,9 @@ void run_prefill(shard* s, shard::Work& wk, const SeqBatch& sb, int T, const flo
 int pick_nsplit(const shard* s, const SeqBatch& sb) {
     int ctx = 1;
     for (int b = 0; b < sb.n; ++b) ctx = ctx > sb.pos[b] + 1 ? ctx : sb.pos[b] + 1;
-    const int units = sb.n * s->m.n_heads / decode_attn_heads_per_group(s->m.n_heads, s->m.n_kv_heads);
-    const int trip = decode_attn_tokens_per_trip(s->m.weight_dtype == SHARD_F32 ? DT_F32 : DT_F16, s->m.head_dim);
+    const int kdt = s->m.weight_dtype == SHARD_F32 ? DT_F32 : DT_F16;
+    const int units = sb.n * s->m.n_heads / decode_attn_heads_per_group(kdt, s->m.head_dim, s->m.n_heads, s->m.n_kv_heads);
+    const int trip = decode_attn_tokens_per_trip(kdt, s->m.head_dim, s->m.n_heads, s->m.n_kv_heads);
     int n = (ctx + trip - 1) / trip;
     const int want = (768 + units - 1) / units;
     if (n > want) n = want;
