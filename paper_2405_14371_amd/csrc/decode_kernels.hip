@@ -595,19 +595,21 @@ __global__ __launch_bounds__(DH) void decode_attn_merge_kernel(DecodeAttn a) {
 // ---------------------------------------------------------------------------------------
 // Grouped-query variant for half caches with dh = 128 and 4..16 query heads per KV head
 // (the 70B shape: 8).  The vector-ALU kernel above is bound by its FMAs and lane reductions
-// once several heads share every key; here the G heads of one KV head are the second
-// dimension of v_mfma_f32_16x16x32_f16: S^T[token][head] = K[token][:] . q[head][:], a tile
-// of 16 tokens per wave and trip, with K fragments loaded straight from the cache (lane
-// (token, g) reads 16 bytes at dh offset 32 j + 8 g, like a weight row of the projection
-// kernel).  P.V stays on the vector ALUs, where it needs no transposed V: lane l owns
-// output columns 2l, 2l+1 of every head, loads those two V elements of each token and reads
-// the tile's probabilities [token][head] back from LDS as broadcasts - no cross-lane
-// reduction before the end.  Grid (nsplit, nb * hkv); the 4 waves of a workgroup take
-// tiles in turn and meet in LDS; slices are merged by decode_attn_merge_kernel as above.
+// once several heads share every key; here both products run on the matrix cores, with the
+// heads of one KV head as the 16-wide dimension and a tile of 16 tokens per wave and trip:
+//   S^T[token][head] = K[token][:] . q[head][:]   4 x v_mfma_f32_16x16x32_f16; lane (token,
+//       g) loads 16 bytes of its key row at dh offset 32 j + 8 g straight from the cache;
+//   O[head][dh] += P[head][token] V[token][dh]    8 x v_mfma_f32_16x16x16_f16; the S^T
+//       accumulators (lane (head, g): tokens 4g..4g+3) are, after exp, exactly the A
+//       operand; V rows go through a 4 KB LDS tile per wave (same addresses as K) and come
+//       back transposed by ds_read_b64_tr_b16 as the B operand.
+// Grid (nsplit, nb * hkv); the 4 waves of a workgroup take tiles in turn and meet in LDS;
+// slices are merged by decode_attn_merge_kernel as above.
 // ---------------------------------------------------------------------------------------
-template <int GH>   // heads computed per KV head: 8 or 16 (heads past hq / hkv are padding)
+typedef _Float16 f16x4_d __attribute__((ext_vector_type(4)));
+
 __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeAttn a, SeqBatch sb) {
-    constexpr int DH = 128, WAVES = 4, KJ = DH / 32;
+    constexpr int DH = 128, WAVES = 4, KJ = DH / 32, NT = DH / 16, GH = 16;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, g = lane >> 4;
     const int G = a.hq / a.kv.hkv;
     const int split = blockIdx.x, b = blockIdx.y / a.kv.hkv, hk = blockIdx.y % a.kv.hkv;
@@ -620,130 +622,136 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeAttn a, SeqB
     const f16_t* __restrict__ vp = static_cast<const f16_t*>(a.kv.v);
     const int32_t* bt = a.kv.block_table + static_cast<size_t>(seq) * a.kv.max_pages;
 
+    // q of head l16 (heads past G are zero): loaded first, so that the loads overlap the block-table
+    // round trip below; scaled by 1/sqrt(dh) in fp32 and rounded to half once
+    float4 qraw[KJ][2];
+    {
+        const float* qp = a.q + (static_cast<size_t>(b) * a.hq + h0 + (l16 < G ? l16 : 0)) * DH + 8 * g;
+#pragma unroll
+        for (int j = 0; j < KJ; ++j) {
+            qraw[j][0] = *reinterpret_cast<const float4*>(qp + 32 * j);
+            qraw[j][1] = *reinterpret_cast<const float4*>(qp + 32 * j + 4);
+        }
+    }
+
+    typedef uint32_t u32x4_d __attribute__((ext_vector_type(4)));
+    u32x4_d ka[KJ], kb[KJ], va[KJ], vb[KJ];   // two register sets, used alternately
     constexpr int PG_CAP = 512;
     __shared__ int32_t s_pg[PG_CAP];
     const int pg_lo = u_begin < u_end ? u_begin / a.kv.page : 0;
     const int pg_n = u_begin < u_end ? (u_end - 1) / a.kv.page - pg_lo + 1 : 0;
     const bool pg_cached = pg_n <= PG_CAP;
+    auto fetch = [&](int t0, u32x4_d (&kr)[KJ], u32x4_d (&vr)[KJ], bool staged) {
+        const int u = min(t0 + l16, u_end - 1);   // past the slice: re-read its last token, masked below
+        const int pg = u / a.kv.page, slot = u - pg * a.kv.page;
+        const int page_id = staged ? s_pg[pg - pg_lo] : bt[pg];
+        const size_t at = ((static_cast<size_t>(page_id) * a.kv.hkv + hk) * a.kv.page + slot) * DH + 8 * g;
+#pragma unroll
+        for (int j = 0; j < KJ; ++j) kr[j] = *reinterpret_cast<const u32x4_d*>(kp + at + 32 * j);
+#pragma unroll
+        for (int j = 0; j < KJ; ++j) vr[j] = *reinterpret_cast<const u32x4_d*>(vp + at + 32 * j);
+    };
+    constexpr int STEP = 16 * WAVES;
+    int t0 = u_begin + 16 * wave;
+    // the slice's page ids go to LDS once (reading the first tile's ids straight from the block
+    // table instead, ahead of the barrier, measured no faster)
     if (pg_cached)
         for (int i = tid; i < pg_n; i += 256) s_pg[i] = bt[pg_lo + i];
     __syncthreads();
+    if (t0 < u_end) fetch(t0, ka, va, pg_cached);
 
-    // q of head l16, scaled by 1/sqrt(dh) in fp32 and rounded to half once
     f16x8_d qf[KJ];
     {
-        const float scale = 1.0f / sqrtf(static_cast<float>(DH));
-        const float* qp = a.q + (static_cast<size_t>(b) * a.hq + h0 + (l16 < G ? l16 : 0)) * DH + 8 * g;
+        const float scale = l16 < G ? 1.0f / sqrtf(static_cast<float>(DH)) : 0.f;
 #pragma unroll
-        for (int j = 0; j < KJ; ++j)
+        for (int j = 0; j < KJ; ++j) {
+            const float t[8] = {qraw[j][0].x, qraw[j][0].y, qraw[j][0].z, qraw[j][0].w,
+                                qraw[j][1].x, qraw[j][1].y, qraw[j][1].z, qraw[j][1].w};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) qf[j][e] = l16 < G ? static_cast<f16_t>(qp[32 * j + e] * scale) : static_cast<f16_t>(0.f);
+            for (int e = 0; e < 8; ++e) qf[j][e] = static_cast<f16_t>(t[e] * scale);
+        }
     }
 
     float m = -INFINITY, lsum = 0.f;   // of head l16 (lsum: this lane's tokens only until the end)
-    float o[GH][2];
+    f32x4_d o[NT];                     // O[head 4g + v][dh 16 nt + l16]
 #pragma unroll
-    for (int h = 0; h < GH; ++h) o[h][0] = o[h][1] = 0.f;
-    __shared__ __align__(16) float s_p[WAVES][16][GH];   // the wave's current tile: exp(s - max) as [token][head]
-    __shared__ __align__(16) float s_c[WAVES][GH];       // rescale factor of the running sums per head
+    for (int nt = 0; nt < NT; ++nt) o[nt] = f32x4_d{0.f, 0.f, 0.f, 0.f};
+    __shared__ __align__(16) char s_v[WAVES][16 * DH * 2];   // the wave's V tile [token][dh], 16-byte chunks XOR-swizzled by token
+    __shared__ __align__(16) float s_c[WAVES][GH];           // rescale factor of the running sums per head
 
-    uint4 ka[KJ], kb[KJ];               // two register sets, used alternately
-    uint32_t va[16], vb[16];
-    auto fetch = [&](int t0, uint4 (&kr)[KJ], uint32_t (&vr)[16]) {
-        const int u = min(t0 + l16, u_end - 1);   // past the slice: re-read its last token, masked below
-        const int pg = u / a.kv.page, slot = u - pg * a.kv.page;
-        const int page_id = pg_cached ? s_pg[pg - pg_lo] : bt[pg];
-        const size_t at = ((static_cast<size_t>(page_id) * a.kv.hkv + hk) * a.kv.page + slot) * DH;
+    auto work = [&](int t0, const u32x4_d (&kr)[KJ], const u32x4_d (&vr)[KJ]) {
+        char* sv = s_v[wave];
 #pragma unroll
-        for (int j = 0; j < KJ; ++j) kr[j] = *reinterpret_cast<const uint4*>(kp + at + 32 * j + 8 * g);
-        const int lo = static_cast<int>(static_cast<uint32_t>(at)), hi = static_cast<int>(static_cast<uint32_t>(at >> 32));
-#pragma unroll
-        for (int t = 0; t < 16; ++t) {   // lane t holds the row of token t0 + t
-            const size_t att = (static_cast<size_t>(static_cast<uint32_t>(__builtin_amdgcn_readlane(hi, t))) << 32) |
-                               static_cast<uint32_t>(__builtin_amdgcn_readlane(lo, t));
-            vr[t] = *reinterpret_cast<const uint32_t*>(vp + att + 2 * lane);
-        }
-    };
-    auto work = [&](int t0, const uint4 (&kr)[KJ], const uint32_t (&vr)[16]) {
+        for (int j = 0; j < KJ; ++j)   // token row l16, chunk 4 j + g
+            *reinterpret_cast<u32x4_d*>(sv + l16 * (DH * 2) + (((4 * j + g) ^ l16) << 4)) = vr[j];
         f32x4_d acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int j = 0; j < KJ; ++j)
             acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_d, kr[j]), qf[j], acc, 0, 0, 0);
         // register v of lane (head l16, g) is token t0 + 4 g + v
-        float sv[4], mx = -INFINITY;
+        float sc[4], mx = -INFINITY;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            sv[v] = t0 + 4 * g + v < u_end ? acc[v] : -INFINITY;
-            mx = fmaxf(mx, sv[v]);
+            sc[v] = t0 + 4 * g + v < u_end ? acc[v] : -INFINITY;
+            mx = fmaxf(mx, sc[v]);
         }
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));   // finite: the tile holds at least one token of the slice
         const float mn = fmaxf(m, mx);
         const float corr = __expf(m - mn);        // first tile: exp(-inf) = 0
         float ps = 0.f;
+        f16x4_d pf;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            const float p = __expf(sv[v] - mn);
+            const float p = __expf(sc[v] - mn);
             ps += p;
-            if (l16 < GH) s_p[wave][4 * g + v][l16] = p;
+            pf[v] = static_cast<f16_t>(p);
         }
         lsum = fmaf(lsum, corr, ps);
         m = mn;
-        if (g == 0 && l16 < GH) s_c[wave][l16] = corr;
+        if (g == 0) s_c[wave][l16] = corr;
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the wave reads back what its other lanes wrote
         __builtin_amdgcn_wave_barrier();
-        {
-            float c[GH];
+        const float4 c = *reinterpret_cast<const float4*>(&s_c[wave][4 * g]);   // heads 4g..4g+3: the rows of o
 #pragma unroll
-            for (int h4 = 0; h4 < GH / 4; ++h4) {
-                const float4 t = *reinterpret_cast<const float4*>(&s_c[wave][4 * h4]);
-                c[4 * h4] = t.x; c[4 * h4 + 1] = t.y; c[4 * h4 + 2] = t.z; c[4 * h4 + 3] = t.w;
-            }
-#pragma unroll
-            for (int h = 0; h < GH; ++h) { o[h][0] *= c[h]; o[h][1] *= c[h]; }
+        for (int nt = 0; nt < NT; ++nt) {
+            // B operand V[tokens 4g..4g+3][dh 16 nt + l16]: within 16 lanes, lane x hands in
+            // the address of 4 halfs and lane (x / 4, x % 4) = (q, e) receives element e of
+            // what lanes q, q + 4, q + 8, q + 12 pointed at; so lane x points at token
+            // 4 g + x / 4, features 16 nt + 4 (x % 4) .. + 3.
+            typedef short i16x4_t __attribute__((ext_vector_type(4)));
+            const int r = 4 * g + (l16 >> 2), d = 16 * nt + 4 * (l16 & 3);
+            const char* at = sv + r * (DH * 2) + (((d >> 3) ^ r) << 4) + (d & 7) * 2;
+            const i16x4_t vt = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4_t*)(at));
+            o[nt][0] *= c.x; o[nt][1] *= c.y; o[nt][2] *= c.z; o[nt][3] *= c.w;
+            o[nt] = __builtin_amdgcn_mfma_f32_16x16x16f16(pf, __builtin_bit_cast(f16x4_d, vt), o[nt], 0, 0, 0);
         }
-#pragma unroll
-        for (int t = 0; t < 16; ++t) {
-            typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-            const h2 vv = __builtin_bit_cast(h2, vr[t]);
-            const float v0 = static_cast<float>(vv[0]), v1 = static_cast<float>(vv[1]);
-#pragma unroll
-            for (int h4 = 0; h4 < GH / 4; ++h4) {
-                const float4 pr = *reinterpret_cast<const float4*>(&s_p[wave][t][4 * h4]);
-                o[4 * h4][0] = fmaf(pr.x, v0, o[4 * h4][0]);         o[4 * h4][1] = fmaf(pr.x, v1, o[4 * h4][1]);
-                o[4 * h4 + 1][0] = fmaf(pr.y, v0, o[4 * h4 + 1][0]); o[4 * h4 + 1][1] = fmaf(pr.y, v1, o[4 * h4 + 1][1]);
-                o[4 * h4 + 2][0] = fmaf(pr.z, v0, o[4 * h4 + 2][0]); o[4 * h4 + 2][1] = fmaf(pr.z, v1, o[4 * h4 + 2][1]);
-                o[4 * h4 + 3][0] = fmaf(pr.w, v0, o[4 * h4 + 3][0]); o[4 * h4 + 3][1] = fmaf(pr.w, v1, o[4 * h4 + 3][1]);
-            }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the next tile overwrites s_p
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the next tile overwrites s_v and s_c
         __builtin_amdgcn_wave_barrier();
     };
-    constexpr int STEP = 16 * WAVES;
-    int t0 = u_begin + 16 * wave;
-    if (t0 < u_end) fetch(t0, ka, va);
     while (t0 < u_end) {
-        if (t0 + STEP < u_end) fetch(t0 + STEP, kb, vb);
+        if (t0 + STEP < u_end) fetch(t0 + STEP, kb, vb, pg_cached);
         work(t0, ka, va);
         t0 += STEP;
         if (t0 >= u_end) break;
-        if (t0 + STEP < u_end) fetch(t0 + STEP, ka, va);
+        if (t0 + STEP < u_end) fetch(t0 + STEP, ka, va, pg_cached);
         work(t0, kb, vb);
         t0 += STEP;
     }
 
     __shared__ float s_m[WAVES][GH], s_l[WAVES][GH];
-    __shared__ __align__(8) float s_o[WAVES][GH][DH];
+    __shared__ float s_o[WAVES][GH][DH];
     lsum += __shfl_xor(lsum, 16, 64);
     lsum += __shfl_xor(lsum, 32, 64);
-    if (g == 0 && l16 < GH) { s_m[wave][l16] = m; s_l[wave][l16] = lsum; }
+    if (g == 0) { s_m[wave][l16] = m; s_l[wave][l16] = lsum; }
 #pragma unroll
-    for (int h = 0; h < GH; ++h) *reinterpret_cast<float2*>(&s_o[wave][h][2 * lane]) = make_float2(o[h][0], o[h][1]);
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) s_o[wave][4 * g + v][16 * nt + l16] = o[nt][v];
     __syncthreads();
 
-    for (int id = tid; id < GH * DH; id += 256) {
+    for (int id = tid; id < G * DH; id += 256) {
         const int h = id / DH, e = id % DH;
-        if (h >= G) break;
         float M = -INFINITY, L = 0.f, O = 0.f;
 #pragma unroll
         for (int w = 0; w < WAVES; ++w) M = fmaxf(M, s_m[w][h]);
@@ -790,10 +798,8 @@ static void launch_da(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st) {
     const int gq = decode_attn_heads_per_group(a.kv_dtype, DH, a.hq, a.kv.hkv);
     const dim3 grid(a.nsplit, a.nb * a.hq / gq), block(256);
     if (decode_attn_gqa(a.kv_dtype, DH, a.hq, a.kv.hkv)) {
-        if (gq <= 8) launch(decode_attn_gqa_kernel<8>, grid, block, 0, st, a, sb);
-        else launch(decode_attn_gqa_kernel<16>, grid, block, 0, st, a, sb);
-    }
-    else if (gq == 4) launch((decode_attn_kernel<KT, DH, 4, 4>), grid, block, 0, st, a, sb);
+        launch(decode_attn_gqa_kernel, grid, block, 0, st, a, sb);
+    } else if (gq == 4) launch((decode_attn_kernel<KT, DH, 4, 4>), grid, block, 0, st, a, sb);
     else if (gq == 2) launch((decode_attn_kernel<KT, DH, 4, 2>), grid, block, 0, st, a, sb);
     else launch((decode_attn_kernel<KT, DH, 4, 1>), grid, block, 0, st, a, sb);
     if (a.nsplit > 1) launch(decode_attn_merge_kernel<DH>, dim3(a.nb * a.hq), dim3(DH), 0, st, a);
@@ -806,6 +812,13 @@ void launch_decode_attn(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st)
         case 64: if (f32) launch_da<float, 64>(a, sb, st); else launch_da<f16_t, 64>(a, sb, st); break;
         default: if (f32) launch_da<float, 128>(a, sb, st); else launch_da<f16_t, 128>(a, sb, st); break;
     }
+}
+
+// Workgroups a launch should have: every workgroup pays a fixed chain of dependent steps
+// (block table, q, first tiles, merge), so beyond what fills the chip more slices cost time
+// (grouped-query kernel at 16 x 8 units, 576 tokens: 3 slices 17.4 us, 6: 18.8, 8: 28.7).
+int decode_attn_target_workgroups(int kv_dtype, int dh, int hq, int hkv) {
+    return decode_attn_gqa(kv_dtype, dh, hq, hkv) ? 512 : 768;
 }
 
 int decode_attn_tokens_per_trip(int kv_dtype, int dh, int hq, int hkv) {

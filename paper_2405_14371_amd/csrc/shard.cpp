@@ -304,7 +304,8 @@ int pick_nsplit(const shard* s, const SeqBatch& sb) {
     const int units = sb.n * s->m.n_heads / decode_attn_heads_per_group(kdt, s->m.head_dim, s->m.n_heads, s->m.n_kv_heads);
     const int trip = decode_attn_tokens_per_trip(kdt, s->m.head_dim, s->m.n_heads, s->m.n_kv_heads);
     int n = (ctx + trip - 1) / trip;
-    const int want = (768 + units - 1) / units;
+    const int target = decode_attn_target_workgroups(kdt, s->m.head_dim, s->m.n_heads, s->m.n_kv_heads);
+    const int want = (target + units - 1) / units;
     if (n > want) n = want;
     if (n > s->nsplit_max) n = s->nsplit_max;
     return n < 1 ? 1 : n;
