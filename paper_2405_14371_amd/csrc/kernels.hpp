@@ -67,7 +67,8 @@ enum Epilogue {
     EPI_QKV = 0,     // RoPE on q,k; q -> q buffer (fp32); k,v -> cache pages
     EPI_RESID = 1,   // out = resid + acc   (fp32)
     EPI_SWIGLU = 2,  // rows (2f, 2f+1) = (gate_f, up_f): out[f] = silu(gate) * up
-    EPI_STORE = 3    // out = acc   (fp32; decode path only: the LM head)
+    EPI_STORE = 3,   // out = acc   (fp32; decode path only: the LM head)
+    EPI_PARTIAL = 4  // out = acc   (fp32; prefill GEMM only: one K slice's partial sums)
 };
 
 // y = W x for a few activation rows (decode): W [N, K] row-major (dtype wt), x fp32 [nb, K].
@@ -138,6 +139,11 @@ struct PrefillGemm {
     int32_t hq;
     KvView kv;
     const float2* rope;
+    // EPI_RESID with few output tiles: scratch for split-K partial sums (may be null) and its
+    // capacity in floats; kslices is set by the launcher
+    float* part;
+    size_t part_cap;
+    int32_t kslices;
 };
 void launch_prefill_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st);
 

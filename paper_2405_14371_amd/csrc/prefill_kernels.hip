@@ -54,6 +54,11 @@ void launch_rmsnorm(const float* x, const float* gain, float eps, void* out, int
 template <typename ET>
 __device__ __forceinline__ void gemm_epilogue(const PrefillGemm& a, const SeqBatch& sb, int m, int n4, const float val[4]) {
     if (m >= a.M || n4 >= a.N) return;
+    if (a.epi == EPI_PARTIAL) {
+        float4 o; o.x = val[0]; o.y = val[1]; o.z = val[2]; o.w = val[3];
+        *reinterpret_cast<float4*>(a.out + static_cast<size_t>(m) * a.N + n4) = o;
+        return;
+    }
     if (a.epi == EPI_RESID) {
         const size_t i = static_cast<size_t>(m) * a.N + n4;
         const float4 r = *reinterpret_cast<const float4*>(a.resid + i);
@@ -337,7 +342,20 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_dma_kernel(PrefillGemm a, S
         src[i] = (is_w ? W : X) + static_cast<size_t>(grow) * a.K + chunk * VEC;
         dst[i] = lds0 + (is_w ? 0 : BN * ROWDW * 4) + cc * 1024;
     }
-    const int ksteps = a.K / BK;
+    // split K: workgroup row blockIdx.y of the grid takes k-steps [ks_lo, ks_hi) and stores its
+    // partial sums to slice blockIdx.y of a.part; splitk_reduce_kernel adds the slices in order
+    PrefillGemm ae = a;
+    int ks_lo = 0, ks_hi = a.K / BK;
+    if (a.kslices > 1) {
+        const int all = a.K / BK, slice = blockIdx.y;
+        ks_lo = static_cast<int>(static_cast<long>(all) * slice / a.kslices);
+        ks_hi = static_cast<int>(static_cast<long>(all) * (slice + 1) / a.kslices);
+        ae.epi = EPI_PARTIAL;
+        ae.out = a.part + static_cast<size_t>(slice) * a.M * a.N;
+#pragma unroll
+        for (int i = 0; i < NPER; ++i) src[i] += static_cast<size_t>(ks_lo) * BK;
+    }
+    const int ksteps = ks_hi - ks_lo;
     auto issue = [&](int ks) {                   // k-step ks -> stage ks % STAGES
         const int kc = ks < ksteps ? ks : ksteps - 1;   // past the end: a harmless reload into a free stage
         const uint32_t sb0 = static_cast<uint32_t>(ks % STAGES) * (STAGE_DW * 4);
@@ -394,7 +412,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_dma_kernel(PrefillGemm a, S
                 const int n4 = n0 + wn * (BN / WN) + i * 32 + vq * 8 + half * 4;
                 const int m = m0 + wm * (BM / WM) + j * 32 + l32;
                 const float val[4] = {acc[i][j][vq * 4], acc[i][j][vq * 4 + 1], acc[i][j][vq * 4 + 2], acc[i][j][vq * 4 + 3]};
-                gemm_epilogue<AT>(a, sb, m, n4, val);
+                gemm_epilogue<AT>(ae, sb, m, n4, val);
             }
 }
 
@@ -411,7 +429,23 @@ static void launch_gemm_dma(const PrefillGemm& a, const SeqBatch& sb, hipStream_
                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         prepared = true;
     }
-    launch(gemm_dma_kernel<T, BN, BM, ROWDW, STAGES, WN, WM>, dim3(grid), dim3(64 * WN * WM), lds, st, a, sb, tiles_m, total);
+    launch(gemm_dma_kernel<T, BN, BM, ROWDW, STAGES, WN, WM>, dim3(grid, a.kslices > 1 ? a.kslices : 1), dim3(64 * WN * WM), lds,
+           st, a, sb, tiles_m, total);
+}
+
+// out = resid + (slice 0 + slice 1 + ...), four elements per thread
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, int slices, size_t slice_elems,
+                                                            const float* resid, float* out) {
+    const size_t i = (static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x) * 4;
+    if (i >= slice_elems) return;
+    float4 acc = *reinterpret_cast<const float4*>(part + i);
+    for (int s = 1; s < slices; ++s) {
+        const float4 t = *reinterpret_cast<const float4*>(part + static_cast<size_t>(s) * slice_elems + i);
+        acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
+    }
+    const float4 r = *reinterpret_cast<const float4*>(resid + i);
+    acc.x += r.x; acc.y += r.y; acc.z += r.z; acc.w += r.w;
+    *reinterpret_cast<float4*>(out + i) = acc;
 }
 
 // Tile choice.  A compute unit holds `occ` workgroups of a variant at once and gets
@@ -467,6 +501,25 @@ static void launch_gemm_f16(const PrefillGemm& a, const SeqBatch& sb, hipStream_
                                         {128, 128, 1, {1000.f, 0.f, 0.f}},
                                         {128, 64, 2, {650.f, 900.f, 0.f}},
                                         {384, 128, 1, {1300.f, 0.f, 0.f}}};  // 256 tiles for 12288 x 1024
+        // A projection back to d_model at small M has too few output tiles for the chip even with
+        // the smallest tile (13B shape, M = 256: 160 tiles): K is split over 3 or 4 workgroup rows,
+        // about two workgroups per compute unit in all, each at least 8 k-steps (measured alone:
+        // O 40 -> 35 us, down 102 -> 76 us; two slices gain nothing over the unsplit launch).
+        if (a.epi == EPI_RESID && a.part) {
+            const long t64 = static_cast<long>((a.M + 63) / 64) * ((a.N + 127) / 128);
+            long S = 512 / t64;
+            if (S > 4) S = 4;
+            if (S > a.K / 64 / 8) S = a.K / 64 / 8;
+            const size_t elems = static_cast<size_t>(a.M) * a.N;
+            if (S >= 3 && elems % 4 == 0 && elems * S <= a.part_cap) {
+                PrefillGemm as = a;
+                as.kslices = static_cast<int32_t>(S);
+                launch_gemm_dma<f16_t, 128, 64, 32, 3, 2, 2>(as, sb, st);
+                launch(splitk_reduce_kernel, dim3(static_cast<unsigned>((elems / 4 + 255) / 256)), dim3(256), 0, st,
+                       static_cast<const float*>(a.part), as.kslices, elems, a.resid, a.out);
+                return;
+            }
+        }
         switch (pick_variant(v, 5, a.M, a.N)) {
             case 0: launch_gemm_dma<f16_t, 256, 256, 32, 2, 4, 2>(a, sb, st); break;
             case 1: launch_gemm_dma<f16_t, 256, 128, 32, 3, 4, 2>(a, sb, st); break;

@@ -64,6 +64,10 @@ struct Timing {
 
 }  // namespace
 
+// Split-K scratch of the prefill GEMM: slices x M x N floats with slices * tiles <= 512 tiles of
+// at most 64 x 128 outputs.
+constexpr size_t SPLITK_FLOATS = 512ull * 64 * 128;
+
 struct shard {
     shard_model_cfg m{};
     shard_kv_cfg kv{};
@@ -88,6 +92,7 @@ struct shard {
         void* f = nullptr;     // [rows, F]      SwiGLU output   (same)
         float* part_o = nullptr;
         float* part_ml = nullptr;
+        float* splitk = nullptr;   // SPLITK_FLOATS floats (half-precision shards only)
         size_t rows = 0;       // activation rows the set can hold
         hipStream_t owner = nullptr;
         bool used = false;
@@ -115,7 +120,7 @@ void free_all(shard* s) {
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     for (auto& w : s->work) {
-        void* wp[] = {w.h, w.q, w.o, w.f, w.part_o, w.part_ml};
+        void* wp[] = {w.h, w.q, w.o, w.f, w.part_o, w.part_ml, w.splitk};
         for (void* p : wp)
             if (p) (void)hipFree(p);
         if (w.done) (void)hipEventDestroy(w.done);
@@ -271,6 +276,7 @@ void run_prefill(shard* s, shard::Work& wk, const SeqBatch& sb, int T, const flo
             launch_prefill_attn(at, sb, st);
         }
         g.A = wk.o; g.W = l.wo; g.N = m.d_model; g.K = s->nq; g.epi = EPI_RESID; g.resid = x; g.out = x_out;
+        g.part = wk.splitk; g.part_cap = wk.splitk ? SPLITK_FLOATS : 0;
         {
             Bracket t(s, SHARD_K_PREFILL_O, st);
             launch_prefill_gemm(g, sb, st);
@@ -607,6 +613,8 @@ int shard_create(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg
         CREATE_TRY(hipMalloc(&w.f, rows * F * sizeof(float)));
         CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&w.part_o), units * s->nsplit_max * dh * sizeof(float)));
         CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&w.part_ml), units * s->nsplit_max * 2 * sizeof(float)));
+        if (model->weight_dtype == SHARD_BF16)   // split-K partial sums of the half-precision prefill GEMM
+            CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&w.splitk), SPLITK_FLOATS * sizeof(float)));
         CREATE_TRY(hipEventCreateWithFlags(&w.done, hipEventDisableTiming));
     }
     s->layer_ev.resize(L + 1);

@@ -89,6 +89,16 @@ def test_grouped_query_decode_attention_on_matrix_cores(lib, hq, hkv, B, T, page
     run_case(lib, cfg, 2, "bf16", B=B, T=T, n_dec=5, seed=41, gains=True, page_size=page)
 
 
+@pytest.mark.parametrize("B,T", [(2, 37), (1, 200), (3, 128)])
+def test_half_prefill_projections_split_k(lib, B, T):
+    """Few output tiles and a long inner dimension: the half-precision O and down projections of
+    the prefill run as 3 or 4 K slices whose partial sums a second kernel adds in slice order
+    (O: K = 2048 = 32 k-steps in 4 slices; down: K = 2368 = 37 k-steps, which 4 slices do not
+    divide evenly)."""
+    cfg = synth.model_cfg("tiny", d_model=256, n_heads=16, n_kv_heads=4, head_dim=128, ffn_dim=2368)
+    run_case(lib, cfg, 2, "bf16", B=B, T=T, n_dec=2, seed=57, gains=True)
+
+
 def test_long_context_spans_many_key_tiles_and_splits(lib):
     cfg = synth.model_cfg("tiny")
     run_case(lib, cfg, 1, "f32", B=1, T=300, n_dec=3, seed=9)
