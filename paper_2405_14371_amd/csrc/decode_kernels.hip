@@ -603,13 +603,18 @@ __global__ __launch_bounds__(DH) void decode_attn_merge_kernel(DecodeAttn a) {
 //       accumulators (lane (head, g): tokens 4g..4g+3) are, after exp, exactly the A
 //       operand; V rows go through a 4 KB LDS tile per wave (same addresses as K) and come
 //       back transposed by ds_read_b64_tr_b16 as the B operand.
-// Grid (nsplit, nb * hkv); the 4 waves of a workgroup take tiles in turn and meet in LDS;
-// slices are merged by decode_attn_merge_kernel as above.
+// Grid (nsplit, nb * hkv); the waves of a workgroup take tiles in turn and meet in LDS.  Every
+// workgroup pays a fixed chain of dependent steps (block table, q, first tile, merge: about
+// 8 us) and sliced contexts a merge launch on top, so up to 1024 tokens one workgroup of 8
+// waves takes the whole context of its (sequence, KV head) (16 x 8 units, 576 tokens: 13.4 us
+// against 12.0 + 4.1 us for four slices and their merge; 16 waves: 15.0 us); longer contexts are
+// cut into slices for 4-wave workgroups and merged by decode_attn_merge_kernel as above.
 // ---------------------------------------------------------------------------------------
 typedef _Float16 f16x4_d __attribute__((ext_vector_type(4)));
 
-__global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeAttn a, SeqBatch sb) {
-    constexpr int DH = 128, WAVES = 4, KJ = DH / 32, NT = DH / 16, GH = 16;
+template <int WAVES, bool TWOSETS>   // TWOSETS: the next tile's K/V are loaded while the current one is worked on
+__global__ __launch_bounds__(64 * WAVES) void decode_attn_gqa_kernel(DecodeAttn a, SeqBatch sb) {
+    constexpr int DH = 128, KJ = DH / 32, NT = DH / 16, GH = 16, THREADS = 64 * WAVES;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, g = lane >> 4;
     const int G = a.hq / a.kv.hkv;
     const int split = blockIdx.x, b = blockIdx.y / a.kv.hkv, hk = blockIdx.y % a.kv.hkv;
@@ -656,7 +661,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeAttn a, SeqB
     // the slice's page ids go to LDS once (reading the first tile's ids straight from the block
     // table instead, ahead of the barrier, measured no faster)
     if (pg_cached)
-        for (int i = tid; i < pg_n; i += 256) s_pg[i] = bt[pg_lo + i];
+        for (int i = tid; i < pg_n; i += THREADS) s_pg[i] = bt[pg_lo + i];
     __syncthreads();
     if (t0 < u_end) fetch(t0, ka, va, pg_cached);
 
@@ -676,11 +681,14 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeAttn a, SeqB
     f32x4_d o[NT];                     // O[head 4g + v][dh 16 nt + l16]
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) o[nt] = f32x4_d{0.f, 0.f, 0.f, 0.f};
-    __shared__ __align__(16) char s_v[WAVES][16 * DH * 2];   // the wave's V tile [token][dh], 16-byte chunks XOR-swizzled by token
+    // one 4 KB V tile [token][dh] per wave (16-byte chunks XOR-swizzled by token); after the
+    // token loop the same memory holds the waves' outputs for 8 heads at a time
+    __shared__ __align__(16) char s_buf[WAVES * 16 * DH * 2];
+    static_assert(WAVES * 16 * DH * 2 >= WAVES * 8 * DH * 4, "output merge fits the V tiles");
     __shared__ __align__(16) float s_c[WAVES][GH];           // rescale factor of the running sums per head
 
     auto work = [&](int t0, const u32x4_d (&kr)[KJ], const u32x4_d (&vr)[KJ]) {
-        char* sv = s_v[wave];
+        char* sv = s_buf + wave * (16 * DH * 2);
 #pragma unroll
         for (int j = 0; j < KJ; ++j)   // token row l16, chunk 4 j + g
             *reinterpret_cast<u32x4_d*>(sv + l16 * (DH * 2) + (((4 * j + g) ^ l16) << 4)) = vr[j];
@@ -729,52 +737,65 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeAttn a, SeqB
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the next tile overwrites s_v and s_c
         __builtin_amdgcn_wave_barrier();
     };
-    while (t0 < u_end) {
-        if (t0 + STEP < u_end) fetch(t0 + STEP, kb, vb, pg_cached);
-        work(t0, ka, va);
-        t0 += STEP;
-        if (t0 >= u_end) break;
-        if (t0 + STEP < u_end) fetch(t0 + STEP, ka, va, pg_cached);
-        work(t0, kb, vb);
-        t0 += STEP;
+    if constexpr (TWOSETS) {
+        while (t0 < u_end) {
+            if (t0 + STEP < u_end) fetch(t0 + STEP, kb, vb, pg_cached);
+            work(t0, ka, va);
+            t0 += STEP;
+            if (t0 >= u_end) break;
+            if (t0 + STEP < u_end) fetch(t0 + STEP, ka, va, pg_cached);
+            work(t0, kb, vb);
+            t0 += STEP;
+        }
+    } else {   // many waves per workgroup: they overlap each other's loads
+        while (t0 < u_end) {
+            work(t0, ka, va);
+            t0 += STEP;
+            if (t0 < u_end) fetch(t0, ka, va, pg_cached);
+        }
     }
 
     __shared__ float s_m[WAVES][GH], s_l[WAVES][GH];
-    __shared__ float s_o[WAVES][GH][DH];
     lsum += __shfl_xor(lsum, 16, 64);
     lsum += __shfl_xor(lsum, 32, 64);
     if (g == 0) { s_m[wave][l16] = m; s_l[wave][l16] = lsum; }
+    float* s_o = reinterpret_cast<float*>(s_buf);   // [WAVES][8][DH]
+    for (int hb = 0; hb < G; hb += 8) {             // heads hb .. hb+7: rows of lane groups g = hb/4, hb/4 + 1
+        __syncthreads();                            // the V tiles (or the previous 8 heads) are done with
+        if ((g >> 1) == (hb >> 3)) {
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
+            for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) s_o[wave][4 * g + v][16 * nt + l16] = o[nt][v];
-    __syncthreads();
-
-    for (int id = tid; id < G * DH; id += 256) {
-        const int h = id / DH, e = id % DH;
-        float M = -INFINITY, L = 0.f, O = 0.f;
+                for (int v = 0; v < 4; ++v) s_o[(wave * 8 + 4 * (g & 1) + v) * DH + 16 * nt + l16] = o[nt][v];
+        }
+        __syncthreads();
+        for (int id = tid; id < 8 * DH; id += THREADS) {
+            const int hl = id / DH, h = hb + hl, e = id % DH;
+            if (h >= G) break;
+            float M = -INFINITY, L = 0.f, O = 0.f;
 #pragma unroll
-        for (int w = 0; w < WAVES; ++w) M = fmaxf(M, s_m[w][h]);
-        if (M > -INFINITY) {
+            for (int w = 0; w < WAVES; ++w) M = fmaxf(M, s_m[w][h]);
+            if (M > -INFINITY) {
 #pragma unroll
-            for (int w = 0; w < WAVES; ++w) {
-                const float wt = __expf(s_m[w][h] - M);  // waves without a tile: exp(-inf) = 0
-                L = fmaf(s_l[w][h], wt, L);
-                O = fmaf(s_o[w][h][e], wt, O);
+                for (int w = 0; w < WAVES; ++w) {
+                    const float wt = __expf(s_m[w][h] - M);  // waves without a tile: exp(-inf) = 0
+                    L = fmaf(s_l[w][h], wt, L);
+                    O = fmaf(s_o[(w * 8 + hl) * DH + e], wt, O);
+                }
             }
-        }
-        const int bh = b * a.hq + h0 + h;
-        if (a.nsplit == 1) {
-            const size_t at = static_cast<size_t>(bh) * DH + e;
-            if (a.o_dtype == DT_F32) static_cast<float*>(a.o)[at] = O / L;
-            else static_cast<f16_t*>(a.o)[at] = static_cast<f16_t>(O / L);
-            continue;
-        }
-        const size_t pbase = static_cast<size_t>(bh) * a.nsplit;
-        a.part_o[(pbase + split) * DH + e] = O;
-        if (e == 0) {
-            a.part_ml[(pbase + split) * 2] = M;
-            a.part_ml[(pbase + split) * 2 + 1] = L;
+            const int bh = b * a.hq + h0 + h;
+            if (a.nsplit == 1) {
+                const size_t at = static_cast<size_t>(bh) * DH + e;
+                if (a.o_dtype == DT_F32) static_cast<float*>(a.o)[at] = O / L;
+                else static_cast<f16_t*>(a.o)[at] = static_cast<f16_t>(O / L);
+                continue;
+            }
+            const size_t pbase = static_cast<size_t>(bh) * a.nsplit;
+            a.part_o[(pbase + split) * DH + e] = O;
+            if (e == 0) {
+                a.part_ml[(pbase + split) * 2] = M;
+                a.part_ml[(pbase + split) * 2 + 1] = L;
+            }
         }
     }
 }
@@ -798,7 +819,8 @@ static void launch_da(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st) {
     const int gq = decode_attn_heads_per_group(a.kv_dtype, DH, a.hq, a.kv.hkv);
     const dim3 grid(a.nsplit, a.nb * a.hq / gq), block(256);
     if (decode_attn_gqa(a.kv_dtype, DH, a.hq, a.kv.hkv)) {
-        launch(decode_attn_gqa_kernel, grid, block, 0, st, a, sb);
+        if (a.nsplit == 1) launch((decode_attn_gqa_kernel<8, false>), grid, dim3(512), 0, st, a, sb);
+        else launch((decode_attn_gqa_kernel<4, true>), grid, block, 0, st, a, sb);
     } else if (gq == 4) launch((decode_attn_kernel<KT, DH, 4, 4>), grid, block, 0, st, a, sb);
     else if (gq == 2) launch((decode_attn_kernel<KT, DH, 4, 2>), grid, block, 0, st, a, sb);
     else launch((decode_attn_kernel<KT, DH, 4, 1>), grid, block, 0, st, a, sb);
@@ -819,6 +841,12 @@ void launch_decode_attn(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st)
 // (grouped-query kernel at 16 x 8 units, 576 tokens: 3 slices 17.4 us, 6: 18.8, 8: 28.7).
 int decode_attn_target_workgroups(int kv_dtype, int dh, int hq, int hkv) {
     return decode_attn_gqa(kv_dtype, dh, hq, hkv) ? 512 : 768;
+}
+
+// Longest context the grouped-query kernel takes in one workgroup per (sequence, KV head)
+// (0: the shape does not use that kernel).
+int decode_attn_single_pass_ctx(int kv_dtype, int dh, int hq, int hkv) {
+    return decode_attn_gqa(kv_dtype, dh, hq, hkv) ? 1024 : 0;
 }
 
 int decode_attn_tokens_per_trip(int kv_dtype, int dh, int hq, int hkv) {

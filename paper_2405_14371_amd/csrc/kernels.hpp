@@ -116,6 +116,7 @@ void launch_decode_attn(const DecodeAttn& a, const SeqBatch& sb, hipStream_t st)
 int decode_attn_heads_per_group(int kv_dtype, int dh, int hq, int hkv);
 int decode_attn_tokens_per_trip(int kv_dtype, int dh, int hq, int hkv);
 int decode_attn_target_workgroups(int kv_dtype, int dh, int hq, int hkv);
+int decode_attn_single_pass_ctx(int kv_dtype, int dh, int hq, int hkv);
 
 // rows of x [M, d] fp32 -> RMSNorm -> out [M, d] in out_dtype
 void launch_rmsnorm(const float* x, const float* gain, float eps, void* out, int32_t out_dtype,

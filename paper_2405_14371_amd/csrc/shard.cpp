@@ -308,6 +308,7 @@ int pick_nsplit(const shard* s, const SeqBatch& sb) {
     for (int b = 0; b < sb.n; ++b) ctx = ctx > sb.pos[b] + 1 ? ctx : sb.pos[b] + 1;
     const int kdt = s->m.weight_dtype == SHARD_F32 ? DT_F32 : DT_F16;
     const int units = sb.n * s->m.n_heads / decode_attn_heads_per_group(kdt, s->m.head_dim, s->m.n_heads, s->m.n_kv_heads);
+    if (ctx <= decode_attn_single_pass_ctx(kdt, s->m.head_dim, s->m.n_heads, s->m.n_kv_heads)) return 1;
     const int trip = decode_attn_tokens_per_trip(kdt, s->m.head_dim, s->m.n_heads, s->m.n_kv_heads);
     int n = (ctx + trip - 1) / trip;
     const int target = decode_attn_target_workgroups(kdt, s->m.head_dim, s->m.n_heads, s->m.n_kv_heads);

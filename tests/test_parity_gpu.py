@@ -79,11 +79,13 @@ def test_matrix_core_decode_rows_per_workgroup(lib, ffn):
 
 
 @pytest.mark.parametrize("hq,hkv,B,T,page", [(8, 2, 1, 37, 16), (8, 1, 6, 150, 16), (8, 1, 2, 300, 3),
-                                             (16, 1, 3, 70, 16), (12, 2, 5, 33, 16), (16, 2, 1, 1, 1)])
+                                             (16, 1, 3, 70, 16), (12, 2, 5, 33, 16), (16, 2, 1, 1, 1),
+                                             (8, 2, 1, 1100, 16), (16, 1, 2, 1030, 16)])
 def test_grouped_query_decode_attention_on_matrix_cores(lib, hq, hkv, B, T, page):
     """Half cache, dh = 128 and 4..16 query heads per KV head: the decode attention kernel that
     puts the heads of a group on the MFMA's second dimension (groups of 4, 8, 16 and 6 heads;
-    contexts of one token, within one 16-token tile, and over several tiles and slices;
+    contexts of one token, within one 16-token tile, over several tiles in one 16-wave workgroup,
+    and past 1024 tokens, where the context is cut into slices that a second kernel merges;
     3-token and 1-token pages)."""
     cfg = synth.model_cfg("tiny", d_model=256, n_heads=hq, n_kv_heads=hkv, head_dim=128, ffn_dim=512)
     run_case(lib, cfg, 2, "bf16", B=B, T=T, n_dec=5, seed=41, gains=True, page_size=page)
