@@ -225,6 +225,91 @@ void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t
 typedef _Float16 f16x8_d __attribute__((ext_vector_type(8)));
 typedef float f32x4_d __attribute__((ext_vector_type(4)));
 
+// Tail shared by the matrix-core projection kernels: the waves' partial accumulators (and sums
+// of squares) meet in LDS in fixed order, then the epilogue.  s_red [WAVES][16 TILES][16],
+// s_val [16 TILES][16] and s_ssq [WAVES][16] are LDS scratch of the caller.
+template <int TILES, int WAVES>
+__device__ __forceinline__ void mfma_linear_finish(const DecodeLinear& a, const SeqBatch& sb, const f32x4_d (&acc)[TILES], float ssq,
+                                                   int row0, int row_end, float* s_red, float* s_val, float* s_ssq) {
+    constexpr int ROWS = 16 * TILES;
+    constexpr int THREADS = 64 * WAVES;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, g = lane >> 4;
+    const int K = a.K;
+    // D[n][b]: register v of a lane is row 4*g + v of its tile, activation row l16
+#pragma unroll
+    for (int t = 0; t < TILES; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) s_red[(wave * ROWS + t * 16 + g * 4 + v) * 16 + l16] = acc[t][v];
+    ssq += __shfl_xor(ssq, 16, 64);   // the four lanes of an activation row hold different k
+    ssq += __shfl_xor(ssq, 32, 64);
+    if (g == 0) s_ssq[wave * 16 + l16] = ssq;
+    __syncthreads();
+    for (int id = tid; id < ROWS * 16; id += THREADS) {
+        const int r = id >> 4, b = id & 15;
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) v += s_red[(w * ROWS + r) * 16 + b];
+        if (a.norm_xb) {
+            float q = 0.f;
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) q += s_ssq[w * 16 + b];
+            v *= 1.0f / sqrtf(q / static_cast<float>(K) + a.eps);
+        }
+        s_val[r * 16 + b] = v;
+    }
+    __syncthreads();
+
+    if (a.epi == EPI_RESID) {
+        for (int id = tid; id < ROWS * 16; id += THREADS) {
+            const int r = id >> 4, b = id & 15, n = row0 + r;
+            if (n < row_end && b < a.nb) {
+                const size_t at = static_cast<size_t>(b) * a.N + n;
+                const float y = a.resid[at] + s_val[r * 16 + b];
+                a.out[at] = y;
+                if (a.out_h) static_cast<f16_t*>(a.out_h)[at] = static_cast<f16_t>(y);
+            }
+        }
+        return;
+    }
+    // pair epilogues: one (row pair j, activation row b) per thread and trip
+    for (int id = tid; id < ROWS * 8; id += THREADS) {   // ROWS/2 row pairs x 16 activation rows
+        const int j = id >> 4, b = id & 15;
+        const int n0 = row0 + 2 * j;
+        if (n0 >= row_end || b >= a.nb) continue;
+        const float v0 = s_val[(2 * j) * 16 + b], v1 = s_val[(2 * j + 1) * 16 + b];
+        if (a.epi == EPI_SWIGLU) {
+            const int F = a.N / 2;
+            static_cast<f16_t*>(a.out_b)[static_cast<size_t>(b) * F + n0 / 2] = static_cast<f16_t>(v0 / (1.0f + expf(-v0)) * v1);
+            continue;
+        }
+        const int dh = a.kv.dh, nq = a.hq * dh, nk = a.kv.hkv * dh;
+        const int pos = sb.pos[b];
+        const int e = n0 % dh;
+        if (n0 < nq + nk) {
+            const float2 cs = a.rope[static_cast<size_t>(pos) * (dh / 2) + e / 2];
+            const float r0 = v0 * cs.x - v1 * cs.y, r1 = v0 * cs.y + v1 * cs.x;
+            if (n0 < nq) {
+                a.q[static_cast<size_t>(b) * nq + n0] = r0;
+                a.q[static_cast<size_t>(b) * nq + n0 + 1] = r1;
+                continue;
+            }
+            const int hk = (n0 - nq) / dh;
+            const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
+            f16_t* kp = static_cast<f16_t*>(a.kv.k);
+            kp[at] = static_cast<f16_t>(r0);
+            kp[at + 1] = static_cast<f16_t>(r1);
+            continue;
+        }
+        const int hk = (n0 - nq - nk) / dh;
+        const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
+        f16_t* vp = static_cast<f16_t*>(a.kv.v);
+        vp[at] = static_cast<f16_t>(v0);
+        vp[at + 1] = static_cast<f16_t>(v1);
+    }
+}
+
+
 template <int TILES, int U, int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLinear a, SeqBatch sb, int rows_wg) {
     constexpr int ROWS = 16 * TILES;
@@ -286,80 +371,117 @@ __global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLi
             }
     }
 
-    // D[n][b]: register v of a lane is row 4*g + v of its tile, activation row l16
-    __shared__ float s_red[WAVES][ROWS][16];
-    __shared__ float s_val[ROWS][16];
-    __shared__ float s_ssq[WAVES][16];
-#pragma unroll
-    for (int t = 0; t < TILES; ++t)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) s_red[wave][t * 16 + g * 4 + v][l16] = acc[t][v];
-    ssq += __shfl_xor(ssq, 16, 64);   // the four lanes of an activation row hold different k
-    ssq += __shfl_xor(ssq, 32, 64);
-    if (g == 0) s_ssq[wave][l16] = ssq;
-    __syncthreads();
-    for (int id = tid; id < ROWS * 16; id += THREADS) {
-        const int r = id >> 4, b = id & 15;
-        float v = 0.f;
-#pragma unroll
-        for (int w = 0; w < WAVES; ++w) v += s_red[w][r][b];
-        if (a.norm_xb) {
-            float q = 0.f;
-#pragma unroll
-            for (int w = 0; w < WAVES; ++w) q += s_ssq[w][b];
-            v *= 1.0f / sqrtf(q / static_cast<float>(K) + a.eps);
-        }
-        s_val[r][b] = v;
-    }
-    __syncthreads();
+    __shared__ float s_red[WAVES * ROWS * 16];
+    __shared__ float s_val[ROWS * 16];
+    __shared__ float s_ssq[WAVES * 16];
+    mfma_linear_finish<TILES, WAVES>(a, sb, acc, ssq, row0, row_end, s_red, s_val, s_ssq);
+}
 
-    if (a.epi == EPI_RESID) {
-        for (int id = tid; id < ROWS * 16; id += THREADS) {
-            const int r = id >> 4, b = id & 15, n = row0 + r;
-            if (n < row_end && b < a.nb) {
-                const size_t at = static_cast<size_t>(b) * a.N + n;
-                const float y = a.resid[at] + s_val[r][b];
-                a.out[at] = y;
-                if (a.out_h) static_cast<f16_t*>(a.out_h)[at] = static_cast<f16_t>(y);
-            }
-        }
-        return;
+// ---------------------------------------------------------------------------------------
+// The same projection with the weights streamed through LDS by direct loads, for workgroups
+// of at most 64 rows (projections back to d_model: 32 rows per workgroup at the 70B width).
+// The register kernel above keeps (TILES + 1) x 16 bytes per lane in flight, about 50 KB per
+// compute unit at 32 rows, and reads 64-byte pieces of 16 rows per instruction; here a ring of
+// STAGES k-steps of 256 elements (512 contiguous bytes per row and load instruction) holds up
+// to 120 KB of loads in flight per compute unit and costs no registers.  Eight waves; per
+// k-step wave w multiplies elements 32 w .. 32 w + 31: one 16-byte LDS read per row tile
+// plus one for the activations (16-byte chunks XOR-swizzled by row, the swizzle applied on the
+// global side), TILES MFMAs, one barrier.  K must be a multiple of 256.
+// ---------------------------------------------------------------------------------------
+template <int TILES, int STAGES>
+__global__ __launch_bounds__(512) void decode_linear_dma_kernel(DecodeLinear a, SeqBatch sb, int rows_wg) {
+    constexpr int WAVES = 8, ROWS = 16 * TILES, BK = 256, ROWB = BK * 2;
+    constexpr int STAGE_B = (ROWS + 16) * ROWB;          // weight rows, then the 16 activation rows
+    constexpr int NLOAD = (ROWS + 16) / 2;               // wave-level loads per stage: two rows each
+    constexpr int NPER = NLOAD / WAVES;
+    static_assert(NLOAD % WAVES == 0, "loads must divide evenly over the waves");
+    static_assert(NPER * (STAGES - 1) < 64, "vmcnt is a 6-bit counter");
+    static_assert(STAGES * STAGE_B >= (WAVES * ROWS * 16 + ROWS * 16 + WAVES * 16) * 4, "the reduction reuses the ring");
+    extern __shared__ __attribute__((aligned(16))) char smem_dl[];
+    const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) void*)smem_dl));
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, g = lane >> 4;
+    const int row0 = blockIdx.x * rows_wg;
+    const int row_end = min(row0 + rows_wg, a.N);
+    const f16_t* __restrict__ W = static_cast<const f16_t*>(a.W);
+    const f16_t* __restrict__ X = static_cast<const f16_t*>(a.xb);
+    const int K = a.K, ksteps = K / BK;
+    const int rot = static_cast<int>((blockIdx.x * 37u) % static_cast<unsigned>(ksteps));   // see the register kernel
+
+    const f16_t* src[NPER];
+    uint32_t dst[NPER];
+#pragma unroll
+    for (int i = 0; i < NPER; ++i) {
+        const int c = wave + WAVES * i;                  // this wave's i-th load of a stage: stage rows 2c, 2c + 1
+        const int r = 2 * c + (lane >> 5), slot = lane & 31;
+        const bool is_w = r < ROWS;
+        const int rr = is_w ? r : r - ROWS;              // row within its tile block: the swizzle key
+        const int chunk = slot ^ (rr & 31);
+        // rows past the workgroup's share re-read its last row, activation rows past the batch row 0:
+        // both feed accumulators that are never stored
+        const int grow = is_w ? min(row0 + r, row_end - 1) : (rr < a.nb ? rr : 0);
+        src[i] = (is_w ? W : X) + static_cast<size_t>(grow) * K + chunk * 8;
+        dst[i] = lds0 + c * 1024;
     }
-    // pair epilogues: one (row pair j, activation row b) per thread and trip
-    for (int id = tid; id < ROWS * 8; id += THREADS) {   // ROWS/2 row pairs x 16 activation rows
-        const int j = id >> 4, b = id & 15;
-        const int n0 = row0 + 2 * j;
-        if (n0 >= row_end || b >= a.nb) continue;
-        const float v0 = s_val[2 * j][b], v1 = s_val[2 * j + 1][b];
-        if (a.epi == EPI_SWIGLU) {
-            const int F = a.N / 2;
-            static_cast<f16_t*>(a.out_b)[static_cast<size_t>(b) * F + n0 / 2] = static_cast<f16_t>(v0 / (1.0f + expf(-v0)) * v1);
-            continue;
+    auto issue = [&](int ks) {                           // k-step ks -> stage ks % STAGES
+        int kc = (ks < ksteps ? ks : ksteps - 1) + rot;  // past the end: a harmless reload into a free stage
+        if (kc >= ksteps) kc -= ksteps;
+        const uint32_t sb0 = static_cast<uint32_t>(ks % STAGES) * STAGE_B;
+#pragma unroll
+        for (int i = 0; i < NPER; ++i) lds_dma16(src[i] + static_cast<size_t>(kc) * BK, dst[i] + sb0);
+    };
+
+    f32x4_d acc[TILES];
+#pragma unroll
+    for (int t = 0; t < TILES; ++t) acc[t] = f32x4_d{0.f, 0.f, 0.f, 0.f};
+    float ssq = 0.f;
+
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s) issue(s);
+    for (int ks = 0; ks < ksteps; ++ks) {
+        wait_vmcnt<NPER*(STAGES - 2)>();                 // this wave's loads of step ks have landed
+        __syncthreads();                                 // ... everyone's; and stage (ks-1) % STAGES is free
+        const char* sW = smem_dl + (ks % STAGES) * STAGE_B;
+        const char* sX = sW + ROWS * ROWB;
+        const int cw = 4 * wave + g;                     // this lane's 16-byte chunk of the step
+        const uint4 xf = *reinterpret_cast<const uint4*>(sX + l16 * ROWB + ((cw ^ l16) << 4));
+        uint4 wf[TILES];
+#pragma unroll
+        for (int t = 0; t < TILES; ++t) {
+            const int r = t * 16 + l16;
+            wf[t] = *reinterpret_cast<const uint4*>(sW + r * ROWB + ((cw ^ (r & 31)) << 4));
         }
-        const int dh = a.kv.dh, nq = a.hq * dh, nk = a.kv.hkv * dh;
-        const int pos = sb.pos[b];
-        const int e = n0 % dh;
-        if (n0 < nq + nk) {
-            const float2 cs = a.rope[static_cast<size_t>(pos) * (dh / 2) + e / 2];
-            const float r0 = v0 * cs.x - v1 * cs.y, r1 = v0 * cs.y + v1 * cs.x;
-            if (n0 < nq) {
-                a.q[static_cast<size_t>(b) * nq + n0] = r0;
-                a.q[static_cast<size_t>(b) * nq + n0 + 1] = r1;
-                continue;
-            }
-            const int hk = (n0 - nq) / dh;
-            const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
-            f16_t* kp = static_cast<f16_t*>(a.kv.k);
-            kp[at] = static_cast<f16_t>(r0);
-            kp[at + 1] = static_cast<f16_t>(r1);
-            continue;
+        issue(ks + STAGES - 1);                          // issued under the latency of the LDS reads
+        if (a.norm_xb) {
+            const f16x8_d h = __builtin_bit_cast(f16x8_d, xf);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ssq = fmaf(static_cast<float>(h[e]), static_cast<float>(h[e]), ssq);
         }
-        const int hk = (n0 - nq - nk) / dh;
-        const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
-        f16_t* vp = static_cast<f16_t*>(a.kv.v);
-        vp[at] = static_cast<f16_t>(v0);
-        vp[at + 1] = static_cast<f16_t>(v1);
+#pragma unroll
+        for (int t = 0; t < TILES; ++t)
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_d, wf[t]), __builtin_bit_cast(f16x8_d, xf),
+                                                            acc[t], 0, 0, 0);
     }
+    wait_vmcnt<0>();                                     // the reloads past the end
+    __syncthreads();                                     // the ring is free: it becomes the reduction's scratch
+    float* s_red = reinterpret_cast<float*>(smem_dl);
+    float* s_val = s_red + WAVES * ROWS * 16;
+    float* s_ssq = s_val + ROWS * 16;
+    mfma_linear_finish<TILES, WAVES>(a, sb, acc, ssq, row0, row_end, s_red, s_val, s_ssq);
+}
+
+template <int TILES, int STAGES>
+static void launch_dl_dma(const DecodeLinear& a, const SeqBatch& sb, dim3 grid, int rows, hipStream_t st) {
+    constexpr size_t lds = static_cast<size_t>(STAGES) * (16 * TILES + 16) * 512;
+    static_assert(lds <= 160 * 1024, "LDS of a compute unit");
+    static bool prepared = false;  // more than 64 KB of LDS per workgroup is an opt-in
+    if (!prepared) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(decode_linear_dma_kernel<TILES, STAGES>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        prepared = true;
+    }
+    launch((decode_linear_dma_kernel<TILES, STAGES>), grid, dim3(512), lds, st, a, sb, rows);
 }
 
 void launch_decode_linear_mfma(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
@@ -373,6 +495,19 @@ void launch_decode_linear_mfma(const DecodeLinear& a, const SeqBatch& sb, hipStr
     rows += rows & 1;   // the pair epilogues need even row offsets
     if (rows < 16) rows = 16;
     const dim3 grid((a.N + rows - 1) / rows);
+    // Weights through an LDS ring of direct loads - unless the row pitch is a power of two: then
+    // the rows of a workgroup sit in the same few memory channels, and a workgroup that moves in
+    // lockstep from barrier to barrier asks them all at once (70B QKV, K = 8192: 31 -> 44 us, while
+    // K = 28672, 13824, 11008 and 5120 gain 9..20 %); the register kernel's waves drift apart.
+    if (rows <= 64 && a.K % 256 == 0 && a.K / 256 >= 8 && (a.K & (a.K - 1)) != 0) {
+        switch ((rows + 15) / 16) {
+            case 1: launch_dl_dma<1, 8>(a, sb, grid, rows, st); break;
+            case 2: launch_dl_dma<2, 6>(a, sb, grid, rows, st); break;
+            case 3: launch_dl_dma<3, 4>(a, sb, grid, rows, st); break;
+            default: launch_dl_dma<4, 3>(a, sb, grid, rows, st); break;
+        }
+        return;
+    }
     switch ((rows + 15) / 16) {   // one K block in flight per wave; 8 waves split K, 16 for tall workgroups
         case 1: launch((decode_linear_mfma_kernel<1, 1, 8>), grid, dim3(512), 0, st, a, sb, rows); break;
         case 2: launch((decode_linear_mfma_kernel<2, 1, 8>), grid, dim3(512), 0, st, a, sb, rows); break;

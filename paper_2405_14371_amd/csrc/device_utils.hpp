@@ -95,6 +95,18 @@ __device__ __forceinline__ float group_sum(float v) {
     return v;
 }
 
+// Direct global -> LDS load (global_load_lds_dwordx4, gfx950): lds_byte (wave-uniform) goes to M0
+// and lane l's 16 bytes land at lds_byte + 16 * l; no registers are occupied while the load is
+// in flight.  Inline assembly because the compiler, for its own direct-to-LDS builtin, waits for
+// every outstanding load before any LDS read; users wait explicitly with wait_vmcnt.
+__device__ __forceinline__ void lds_dma16(const void* g, uint32_t lds_byte) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_byte) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 // pos[b] = tokens already cached for seq[b] before this call.
 struct SeqBatch {
     int32_t n;

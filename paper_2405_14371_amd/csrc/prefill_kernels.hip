@@ -292,14 +292,6 @@ static void launch_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st
 // The loads are inline assembly because the compiler, for its own direct-to-LDS builtin,
 // waits for every outstanding load before any LDS read; waits here are explicit.
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ void lds_dma16(const void* g, uint32_t lds_byte) {
-    // lds_byte (wave-uniform) -> M0; lane l's 16 bytes land at lds_byte + 16 * l
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_byte) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
 
 template <typename T, int BN, int BM, int ROWDW, int STAGES, int WN, int WM>
 __global__ __launch_bounds__(64 * WN * WM) void gemm_dma_kernel(PrefillGemm a, SeqBatch sb, int tiles_m, int tiles_total) {

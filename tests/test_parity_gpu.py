@@ -78,6 +78,17 @@ def test_matrix_core_decode_rows_per_workgroup(lib, ffn):
     run_case(lib, cfg, 1, "bf16", B=6, T=8, n_dec=2, seed=33, gains=True)
 
 
+@pytest.mark.parametrize("ffn,B", [(2304, 6), (5120, 5), (7680, 16), (5120, 19)])
+def test_matrix_core_decode_weights_through_lds_ring(lib, ffn, B):
+    """Inner dimensions of 2048 and more (multiples of 256, not a power of two: d_model 2304 and
+    the FFN widths) with at most 64 rows per workgroup: the batched decode projections stream
+    their weights through an LDS ring of direct loads (the O projection, K = 2048, does not);
+    16, 18, 40 and 60 rows per workgroup (1 to 4 row tiles, with partial tiles), a down
+    projection whose 9 k-steps barely exceed the ring, batches of 5..19."""
+    cfg = synth.model_cfg("tiny", d_model=2304, n_heads=16, n_kv_heads=4, head_dim=128, ffn_dim=ffn)
+    run_case(lib, cfg, 1, "bf16", B=B, T=4, n_dec=2, seed=61, gains=True)
+
+
 @pytest.mark.parametrize("hq,hkv,B,T,page", [(8, 2, 1, 37, 16), (8, 1, 6, 150, 16), (8, 1, 2, 300, 3),
                                              (16, 1, 3, 70, 16), (12, 2, 5, 33, 16), (16, 2, 1, 1, 1),
                                              (8, 2, 1, 1100, 16), (16, 1, 2, 1030, 16)])
