@@ -244,6 +244,34 @@ def test_runtime_errors_leave_state_unchanged(lib):
     sh.close()
 
 
+def test_create_rejects_16_bit_weights_outside_the_range_of_half(lib):
+    """bf16 matrices live on the device as IEEE half with the RMSNorm gains folded in: a weight
+    above 65504, or a weight whose product with its gain is, makes shard_create fail."""
+    cfg = synth.model_cfg("tiny")
+
+    def create(mutate):
+        layers = H.make_layers(cfg, 29, 1, "bf16")
+        mutate(layers[0])
+        with pytest.raises(lib.ShardError) as e:
+            H.gpu_shard(lib, cfg, layers, "bf16", max_seqs=1, max_seq_len=16, page_size=4)
+        assert e.value.code == lib.SHARD_E_INVAL and "65504" in str(e.value), e.value
+
+    def big_weight(lw):
+        w = lw["w_down"].copy()
+        w.flat[5] = 65536.0           # exact in bf16, above half's largest finite value
+        lw["w_down"] = w
+
+    def big_gain(lw):
+        g = lw["g_ffn"].copy()
+        g[7] = 1e7                    # times weights of about 0.02
+        lw["g_ffn"] = g
+
+    create(big_weight)
+    create(big_gain)
+    ok = H.gpu_shard(lib, cfg, H.make_layers(cfg, 29, 1, "bf16"), "bf16", max_seqs=1, max_seq_len=16, page_size=4)
+    ok.close()
+
+
 def test_profile_and_kernel_timing(lib):
     cfg = synth.model_cfg("tiny")
     layers = H.make_layers(cfg, 29, 2)
