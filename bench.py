@@ -41,6 +41,8 @@ WORKLOADS = {
     # the same eight sequences as one batch of 8: one pass over the weights serves all of them
     "llama2-13b-l0-19-bf16-b8-fused-p256-d128": dict(model="13b", layers=20, dtype="bf16", B=8, T=256, n_dec=128),
     "llama2-70b-l0-19-bf16-b16-p512-d128": dict(model="70b", layers=20, dtype="bf16", B=16, T=512, n_dec=128),
+    # the paper's own request shape (Sec. 5.1: 32 input tokens, 96 generated) on the whole 7B stack
+    "llama2-7b-32l-bf16-b1-p32-d96": dict(model="7b", layers=32, dtype="bf16", B=1, T=32, n_dec=96),
     "tiny-2l-fp32-b1-p32-d16": dict(model="tiny", layers=2, dtype="f32", B=1, T=32, n_dec=16),
 }
 DEFAULT_WORKLOAD = "llama2-7b-l0-7-fp32-b1-p512-d128"
