@@ -492,7 +492,8 @@ static void launch_gemm_f16(const PrefillGemm& a, const SeqBatch& sb, hipStream_
                                         {256, 128, 1, {1250.f, 0.f, 0.f}},
                                         {128, 128, 1, {1000.f, 0.f, 0.f}},
                                         {128, 64, 2, {650.f, 900.f, 0.f}},
-                                        {384, 128, 1, {1300.f, 0.f, 0.f}}};  // 256 tiles for 12288 x 1024
+                                        {384, 128, 1, {1300.f, 0.f, 0.f}},   // 256 tiles for 12288 x 1024
+                                        {64, 64, 1, {330.f, 0.f, 0.f}}};     // a few dozen rows: more workgroups stream the weights
         // A projection back to d_model at small M has too few output tiles for the chip even with
         // the smallest tile (13B shape, M = 256: 160 tiles): K is split over 3 or 4 workgroup rows,
         // about two workgroups per compute unit in all, each at least 8 k-steps (measured alone:
@@ -512,7 +513,8 @@ static void launch_gemm_f16(const PrefillGemm& a, const SeqBatch& sb, hipStream_
                 return;
             }
         }
-        switch (pick_variant(v, 5, a.M, a.N)) {
+        switch (pick_variant(v, 6, a.M, a.N)) {
+            case 5: launch_gemm_dma<f16_t, 64, 64, 32, 6, 2, 2>(a, sb, st); break;
             case 0: launch_gemm_dma<f16_t, 256, 256, 32, 2, 4, 2>(a, sb, st); break;
             case 1: launch_gemm_dma<f16_t, 256, 128, 32, 3, 4, 2>(a, sb, st); break;
             case 2: launch_gemm_dma<f16_t, 128, 128, 32, 3, 2, 2>(a, sb, st); break;
