@@ -112,6 +112,13 @@ def test_half_prefill_projections_split_k(lib, B, T):
     run_case(lib, cfg, 2, "bf16", B=B, T=T, n_dec=2, seed=57, gains=True)
 
 
+def test_sixteen_thousand_tokens_in_one_token_pages(lib):
+    """A context of 16,500 tokens in pages of one token: the block-table row is longer than the
+    prefill attention kernel's LDS copy (it falls back to the kernel that reads pages from global
+    memory) and a decode slice spans more pages than its LDS page cache holds."""
+    run_case(lib, synth.model_cfg("tiny"), 1, "f32", B=1, T=16500, n_dec=2, seed=71, page_size=1)
+
+
 def test_long_context_spans_many_key_tiles_and_splits(lib):
     cfg = synth.model_cfg("tiny")
     run_case(lib, cfg, 1, "f32", B=1, T=300, n_dec=3, seed=9)
