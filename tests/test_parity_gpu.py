@@ -112,6 +112,23 @@ def test_half_prefill_projections_split_k(lib, B, T):
     run_case(lib, cfg, 2, "bf16", B=B, T=T, n_dec=2, seed=57, gains=True)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_largest_batch_of_64_sequences(lib, dtype):
+    """SHARD_MAX_BATCH sequences in one call (fp32: eight passes of 8 rows; bf16: four groups
+    of 16 on the matrix cores), and one more is refused before anything is launched."""
+    cfg = synth.model_cfg("tiny", d_model=512, n_heads=8, n_kv_heads=2, head_dim=64, ffn_dim=1024)
+    run_case(lib, cfg, 1, dtype, B=64, T=3, n_dec=2, seed=73, gains=True)
+    layers = H.make_layers(cfg, 73, 1, dtype)
+    sh = H.gpu_shard(lib, cfg, layers, dtype, max_seqs=65, max_seq_len=8, page_size=4, max_batch_tokens=65)
+    ids = [sh.seq_alloc() for _ in range(65)]
+    x = H.to_dev(np.zeros((65, 1, cfg["d_model"]), np.float32))
+    with pytest.raises(lib.ShardError) as e:
+        sh.prefill(ids, 1, x, x.clone())
+    assert e.value.code == lib.SHARD_E_INVAL
+    assert all(sh.seq_len(i) == 0 for i in ids)
+    sh.close()
+
+
 def test_sixteen_thousand_tokens_in_one_token_pages(lib):
     """A context of 16,500 tokens in pages of one token: the block-table row is longer than the
     prefill attention kernel's LDS copy (it falls back to the kernel that reads pages from global
