@@ -471,10 +471,12 @@ static void launch_gemm_f32(const PrefillGemm& a, const SeqBatch& sb, hipStream_
     if (a.K % 16 == 0) {  // direct-to-LDS variants (k-step of 16 or 32)
         static const GemmVariant v[] = {{128, 128, 2, {100.f, 142.f, 0.f}},
                                         {128, 64, 3, {125.f, 120.f, 116.f}},
-                                        {128, 64, 2, {116.f, 131.f, 0.f}}};
-        switch (pick_variant(v, a.K % 32 == 0 ? 3 : 2, a.M, a.N)) {
+                                        {192, 64, 2, {118.f, 138.f, 0.f}},   // 12288 x 512: two tiles per unit, both resident
+                                        {128, 64, 2, {116.f, 131.f, 0.f}}};  // k-step 32
+        switch (pick_variant(v, a.K % 32 == 0 ? 4 : 3, a.M, a.N)) {
             case 0: launch_gemm_dma<float, 128, 128, 16, 4, 2, 2>(a, sb, st); break;
             case 1: launch_gemm_dma<float, 128, 64, 16, 4, 2, 2>(a, sb, st); break;
+            case 2: launch_gemm_dma<float, 192, 64, 16, 4, 2, 2>(a, sb, st); break;
             default: launch_gemm_dma<float, 128, 64, 32, 3, 2, 2>(a, sb, st); break;
         }
         return;
