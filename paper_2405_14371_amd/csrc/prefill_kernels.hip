@@ -472,11 +472,13 @@ static void launch_gemm_f32(const PrefillGemm& a, const SeqBatch& sb, hipStream_
         static const GemmVariant v[] = {{128, 128, 2, {100.f, 142.f, 0.f}},
                                         {128, 64, 3, {125.f, 120.f, 116.f}},
                                         {192, 64, 2, {118.f, 138.f, 0.f}},   // 12288 x 512: two tiles per unit, both resident
+                                        {192, 128, 2, {136.f, 144.f, 0.f}},  // 22016 x 512: 460 tiles, at most two per unit
                                         {128, 64, 2, {116.f, 131.f, 0.f}}};  // k-step 32
-        switch (pick_variant(v, a.K % 32 == 0 ? 4 : 3, a.M, a.N)) {
+        switch (pick_variant(v, a.K % 32 == 0 ? 5 : 4, a.M, a.N)) {
             case 0: launch_gemm_dma<float, 128, 128, 16, 4, 2, 2>(a, sb, st); break;
             case 1: launch_gemm_dma<float, 128, 64, 16, 4, 2, 2>(a, sb, st); break;
             case 2: launch_gemm_dma<float, 192, 64, 16, 4, 2, 2>(a, sb, st); break;
+            case 3: launch_gemm_dma<float, 192, 128, 16, 4, 2, 2>(a, sb, st); break;
             default: launch_gemm_dma<float, 128, 64, 32, 3, 2, 2>(a, sb, st); break;
         }
         return;

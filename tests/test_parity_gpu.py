@@ -130,10 +130,10 @@ def test_largest_batch_of_64_sequences(lib, dtype):
 
 
 def test_fp32_prefill_with_192_row_weight_tiles(lib):
-    """512 tokens against 12288 QKV rows and 11008 gate/up rows (a ragged last tile): the shapes
-    for which the fp32 prefill GEMM takes its 192 x 64 tiles, with a short inner dimension so
-    that the oracle stays quick."""
-    cfg = synth.model_cfg("tiny", d_model=64, n_heads=32, n_kv_heads=32, head_dim=128, ffn_dim=5504)
+    """512 tokens against 12288 QKV rows and 22016 gate/up rows (a ragged last tile): the shapes
+    for which the fp32 prefill GEMM takes its 192 x 64 and 192 x 128 tiles, with a short inner
+    dimension so that the oracle stays quick."""
+    cfg = synth.model_cfg("tiny", d_model=64, n_heads=32, n_kv_heads=32, head_dim=128, ffn_dim=11008)
     run_case(lib, cfg, 1, "f32", B=1, T=512, n_dec=1, seed=79, gains=True)
 
 
