@@ -313,7 +313,6 @@ __device__ __forceinline__ void mfma_linear_finish(const DecodeLinear& a, const 
 template <int TILES, int U, int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLinear a, SeqBatch sb, int rows_wg) {
     constexpr int ROWS = 16 * TILES;
-    constexpr int THREADS = 64 * WAVES;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, g = lane >> 4;
     // rows_wg <= ROWS rows per workgroup (even): the launch picks it so that the workgroups

@@ -576,7 +576,6 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(PrefillAttn a, SeqBat
     const KT* __restrict__ kp = static_cast<const KT*>(a.kv.k);
     const KT* __restrict__ vp = static_cast<const KT*>(a.kv.v);
     const int ctx = P + a.T;
-    const int page = a.kv.page, hkv = a.kv.hkv;
 
     const int t_q = qt * 32 + l32;                // this lane's query row within the call
     const int t_ld = min(t_q, a.T - 1);
@@ -683,7 +682,6 @@ __global__ __launch_bounds__(256) void prefill_attn_f16_kernel(PrefillAttn a, Se
     const f16_t* __restrict__ kp = static_cast<const f16_t*>(a.kv.k);
     const f16_t* __restrict__ vp = static_cast<const f16_t*>(a.kv.v);
     const int ctx = P + a.T;
-    const int page = a.kv.page, hkv = a.kv.hkv;
 
     const int t_q = qt * 32 + l32;
     const int t_ld = min(t_q, a.T - 1);
