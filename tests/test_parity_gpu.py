@@ -112,6 +112,22 @@ def test_half_prefill_projections_split_k(lib, B, T):
     run_case(lib, cfg, 2, "bf16", B=B, T=T, n_dec=2, seed=57, gains=True)
 
 
+def test_batched_half_precision_paths_are_deterministic(lib):
+    """Two shards from the same weights, the same calls: bit-identical outputs through the
+    split-K prefill projections, the matrix-core decode projections (register and LDS-ring
+    variants) and grouped-query attention, whose partial results all meet in a fixed order."""
+    cfg = synth.model_cfg("tiny", d_model=2304, n_heads=16, n_kv_heads=4, head_dim=128, ffn_dim=2368)
+    layers = H.make_layers(cfg, 83, 1, "bf16", True)
+    chunks = chunks_for(cfg, 83, 6, 40, 3)
+    outs = []
+    for _ in range(2):
+        sh = H.gpu_shard(lib, cfg, layers, "bf16", max_seqs=6, max_seq_len=48, page_size=16, max_batch_tokens=240)
+        outs.append(H.run_gpu(sh, [sh.seq_alloc() for _ in range(6)], chunks))
+        sh.close()
+    for a, b in zip(*outs):
+        np.testing.assert_array_equal(a, b)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_largest_batch_of_64_sequences(lib, dtype):
     """SHARD_MAX_BATCH sequences in one call (fp32: eight passes of 8 rows; bf16: four groups
