@@ -797,8 +797,8 @@ static void launch_pa(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st) 
 
 // ---------------------------------------------------------------------------------------
 // Prefill attention with key/value tiles staged in LDS (head_dim 64 or 128).
-// A workgroup owns 128 consecutive query rows of one (sequence, head): QT = 4 waves take one
-// 32-row query tile each, and KS groups of such waves split the 32-key blocks between them
+// A workgroup owns 32 QT (128 or 64) consecutive query rows of one (sequence, head): QT waves
+// take one 32-row query tile each, and KS groups of such waves split the 32-key blocks between them
 // (group g takes blocks g, g + KS, ...), each with its own running max / sum / output, merged
 // at the end in group order.  The waves of a group share every K and V tile: the tile is
 // fetched once, straight from global memory into a ring of LDS stages (16 bytes per lane,
@@ -811,9 +811,9 @@ static void launch_pa(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st) 
 // Same arithmetic as the kernels above: S^T = K Q^T and O^T = V^T P^T on the matrix cores,
 // softmax per query column in fp32.
 // ---------------------------------------------------------------------------------------
-template <typename KT, int DH, int KS, int STAGES>
-__global__ __launch_bounds__(256 * KS) void prefill_attn_lds_kernel(PrefillAttn a, SeqBatch sb) {
-    constexpr int QT = 4;
+template <typename KT, int DH, int KS, int STAGES, int QT>
+__global__ __launch_bounds__(64 * QT * KS) void prefill_attn_lds_kernel(PrefillAttn a, SeqBatch sb) {
+    constexpr int QB = 32 * QT;                   // query rows per workgroup
     constexpr bool F16 = sizeof(KT) == 2;
     constexpr int VEC = 16 / sizeof(KT);
     constexpr int CHR = DH / VEC;                 // 16-byte chunks per row
@@ -843,11 +843,11 @@ __global__ __launch_bounds__(256 * KS) void prefill_attn_lds_kernel(PrefillAttn 
     const KT* __restrict__ vp = static_cast<const KT*>(a.kv.v);
 
     // blocks this workgroup walks: up to the diagonal of its last query row
-    const int last_row_wg = min(qg * 128 + 127, a.T - 1);
+    const int last_row_wg = min(qg * QB + QB - 1, a.T - 1);
     const int nblk_wg = (P + last_row_wg) / 32 + 1;
     const int steps = (nblk_wg + KS - 1) / KS;
     const int npages = (ctx - 1) / a.kv.page + 1;
-    for (int i = tid; i < npages; i += 256 * KS) s_bt[i] = bt[i];
+    for (int i = tid; i < npages; i += 64 * QT * KS) s_bt[i] = bt[i];
     __syncthreads();
 
     // this lane's share of a stage: NPER loads, each 16 bytes of one K or V row
@@ -884,7 +884,7 @@ __global__ __launch_bounds__(256 * KS) void prefill_attn_lds_kernel(PrefillAttn 
     };
 
     // query fragments (scaled), this wave's 32 rows
-    const int t_q = qg * 128 + wq * 32 + l32;
+    const int t_q = qg * QB + wq * 32 + l32;
     const int t_ld = min(t_q, a.T - 1);
     const size_t qrow = (static_cast<size_t>(b) * a.T + t_ld) * a.hq * DH + h * DH;
     const float scale = 1.0f / sqrtf(static_cast<float>(DH));
@@ -916,7 +916,7 @@ __global__ __launch_bounds__(256 * KS) void prefill_attn_lds_kernel(PrefillAttn 
     float m_run = -INFINITY, l_run = 0.f;
     const int pos_q = P + t_q;
     // diagonal of this wave's tile; a tile that starts past the last row has nothing to do
-    const int last_key = qg * 128 + wq * 32 < a.T ? P + min(qg * 128 + wq * 32 + 31, a.T - 1) : -1;
+    const int last_key = qg * QB + wq * 32 < a.T ? P + min(qg * QB + wq * 32 + 31, a.T - 1) : -1;
 
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s) issue(s);
@@ -1062,20 +1062,32 @@ __global__ __launch_bounds__(256 * KS) void prefill_attn_lds_kernel(PrefillAttn 
         }
 }
 
-template <typename KT, int DH, int KS, int STAGES>
-static void launch_pa_lds(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st) {
+template <typename KT, int DH, int KS, int STAGES, int QT>
+static void launch_pa_lds_q(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st) {
     constexpr size_t lds = 2048 * 4 + static_cast<size_t>(KS) * STAGES * 2 * 32 * DH * sizeof(KT);
     static_assert(lds <= 160 * 1024, "LDS of a compute unit");
-    static_assert(KS == 1 || static_cast<size_t>(KS) * STAGES * 2 * 32 * DH * sizeof(KT) >= 4 * (DH / 32 * 16 + 2) * 64 * 4,
+    static_assert(KS == 1 || static_cast<size_t>(KS) * STAGES * 2 * 32 * DH * sizeof(KT) >= QT * (DH / 32 * 16 + 2) * 64 * 4,
                   "the merge buffer lives in the ring");
     static bool prepared = false;
     if (!prepared) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_attn_lds_kernel<KT, DH, KS, STAGES>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_attn_lds_kernel<KT, DH, KS, STAGES, QT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         prepared = true;
     }
-    const dim3 grid((a.T + 127) / 128, a.hq, a.B);
-    launch(prefill_attn_lds_kernel<KT, DH, KS, STAGES>, grid, dim3(256 * KS), lds, st, a, sb);
+    const dim3 grid((a.T + 32 * QT - 1) / (32 * QT), a.hq, a.B);
+    launch(prefill_attn_lds_kernel<KT, DH, KS, STAGES, QT>, grid, dim3(64 * QT * KS), lds, st, a, sb);
+}
+
+// Query rows per workgroup: 128, or 64 when 128-row blocks would not even give every compute
+// unit a workgroup (7B shape, 512 tokens, one sequence: 128 workgroups; 64-row blocks make it
+// 256 and the fp32 kernel 82 -> 58 us).  With a workgroup per unit already, the smaller blocks'
+// lower K/V reuse costs more than the better balance of the causal triangle gains (half
+// precision, 1024 tokens: 43 -> 72 us).
+template <typename KT, int DH, int KS, int STAGES>
+static void launch_pa_lds(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st) {
+    const long wgs128 = static_cast<long>((a.T + 127) / 128) * a.hq * a.B;
+    if (wgs128 < 256) launch_pa_lds_q<KT, DH, KS, STAGES, 2>(a, sb, st);
+    else launch_pa_lds_q<KT, DH, KS, STAGES, 4>(a, sb, st);
 }
 
 void launch_prefill_attn(const PrefillAttn& a, const SeqBatch& sb, hipStream_t st) {
