@@ -474,6 +474,21 @@ static void launch_gemm_f32(const PrefillGemm& a, const SeqBatch& sb, hipStream_
                                         {192, 64, 2, {118.f, 138.f, 0.f}},   // 12288 x 512: two tiles per unit, both resident
                                         {192, 128, 2, {136.f, 144.f, 0.f}},  // 22016 x 512: 460 tiles, at most two per unit
                                         {128, 64, 2, {116.f, 131.f, 0.f}}};  // k-step 32
+        // at most one 128 x 64 tile per compute unit (projections back to d_model at M = 512): two
+        // K slices put two workgroups on every unit (alone: O 145 -> 136 us, down 364 -> 343 us
+        // with the reduction; three slices lose)
+        if (a.epi == EPI_RESID && a.part) {
+            const long t64 = static_cast<long>((a.M + 63) / 64) * ((a.N + 127) / 128);
+            const size_t elems = static_cast<size_t>(a.M) * a.N;
+            if (t64 > 128 && t64 <= 256 && a.K >= 2048 && elems % 4 == 0 && elems * 2 <= a.part_cap) {
+                PrefillGemm as = a;
+                as.kslices = 2;
+                launch_gemm_dma<float, 128, 64, 16, 4, 2, 2>(as, sb, st);
+                launch(splitk_reduce_kernel, dim3(static_cast<unsigned>((elems / 4 + 255) / 256)), dim3(256), 0, st,
+                       static_cast<const float*>(a.part), 2, elems, a.resid, a.out);
+                return;
+            }
+        }
         switch (pick_variant(v, a.K % 32 == 0 ? 5 : 4, a.M, a.N)) {
             case 0: launch_gemm_dma<float, 128, 128, 16, 4, 2, 2>(a, sb, st); break;
             case 1: launch_gemm_dma<float, 128, 64, 16, 4, 2, 2>(a, sb, st); break;

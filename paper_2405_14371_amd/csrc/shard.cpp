@@ -92,7 +92,7 @@ struct shard {
         void* f = nullptr;     // [rows, F]      SwiGLU output   (same)
         float* part_o = nullptr;
         float* part_ml = nullptr;
-        float* splitk = nullptr;   // SPLITK_FLOATS floats (half-precision shards only)
+        float* splitk = nullptr;   // SPLITK_FLOATS floats
         size_t rows = 0;       // activation rows the set can hold
         hipStream_t owner = nullptr;
         bool used = false;
@@ -614,8 +614,7 @@ int shard_create(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg
         CREATE_TRY(hipMalloc(&w.f, rows * F * sizeof(float)));
         CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&w.part_o), units * s->nsplit_max * dh * sizeof(float)));
         CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&w.part_ml), units * s->nsplit_max * 2 * sizeof(float)));
-        if (model->weight_dtype == SHARD_BF16)   // split-K partial sums of the half-precision prefill GEMM
-            CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&w.splitk), SPLITK_FLOATS * sizeof(float)));
+        CREATE_TRY(hipMalloc(reinterpret_cast<void**>(&w.splitk), SPLITK_FLOATS * sizeof(float)));   // split-K partial sums (prefill GEMM)
         CREATE_TRY(hipEventCreateWithFlags(&w.done, hipEventDisableTiming));
     }
     s->layer_ev.resize(L + 1);

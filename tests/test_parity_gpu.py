@@ -145,6 +145,14 @@ def test_largest_batch_of_64_sequences(lib, dtype):
     sh.close()
 
 
+def test_fp32_prefill_two_k_slices(lib):
+    """512 tokens against a model width of 2304: the O and down projections (K = 2048) have 144
+    tiles of 128 x 64, at most one per compute unit, and run as two K slices plus the ordered
+    reduction."""
+    cfg = synth.model_cfg("tiny", d_model=2304, n_heads=16, n_kv_heads=4, head_dim=128, ffn_dim=2048)
+    run_case(lib, cfg, 1, "f32", B=1, T=512, n_dec=1, seed=89, gains=True)
+
+
 def test_fp32_prefill_with_192_row_weight_tiles(lib):
     """512 tokens against 12288 QKV rows and 22016 gate/up rows (a ragged last tile): the shapes
     for which the fp32 prefill GEMM takes its 192 x 64 and 192 x 128 tiles, with a short inner
