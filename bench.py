@@ -227,7 +227,8 @@ def main():
         "kernel": "gemm_dma_kernel (MFMA projections of shard_prefill)",
         "bound": "mfma", "achieved": round(gm_flops / gm["seconds"] / 1e12, 2), "peak": peak_tf, "unit": "TFLOP/s",
         "frac": round(gm_flops / gm["seconds"] / 1e12 / peak_tf, 4),
-        "launches": gm["launches"], "avg_launch_us": round(gm["seconds"] / max(1, gm["launches"]) * 1e6, 2),
+        # one projection = one GEMM launch, plus the short reduction launch where K is split
+        "launches": 4 * calls_pre, "avg_launch_us": round(gm["seconds"] / (4 * calls_pre) * 1e6, 2),
     }
     kernel_seconds = {k: {"launches": v["launches"], "ms": round(v["seconds"] * 1e3, 3),
                           "avg_us": round(v["seconds"] / max(1, v["launches"]) * 1e6, 2)} for k, v in kt.items()}
