@@ -3,6 +3,7 @@ declares, and rejects bad arguments before it touches a GPU."""
 import ctypes as C
 import os
 import re
+import subprocess
 
 import pytest
 
@@ -127,3 +128,17 @@ def test_synth_is_deterministic_and_bf16_rounding_is_rne():
     assert synth.bf16_bits(np.array([1.0], dtype=np.float32))[0] == 0x3F80
     with pytest.raises(ValueError):
         synth.bf16_bits(np.array([1.0 + 2 ** -20], dtype=np.float32))
+
+
+def test_boundary_from_plain_c(lib, tmp_path):
+    """tests/c/abi_from_c.c: strict C99 against the three headers, linked with libshard.so; it
+    checks a host-only entry point against a closed form and the error path without a GPU."""
+    lib.load()
+    libdir = os.path.dirname(lib.LIB_PATH)
+    exe = str(tmp_path / "abi_from_c")
+    cc = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                         os.path.join(ROOT, "tests", "c", "abi_from_c.c"), "-o", exe, "-L", libdir, "-lshard", "-lm",
+                         "-Wl,-rpath," + libdir], capture_output=True, text=True)
+    assert cc.returncode == 0, cc.stderr
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert run.returncode == 0 and run.stdout.strip() == "ok", (run.returncode, run.stdout, run.stderr)
