@@ -16,6 +16,7 @@
 
 #include <cstddef>
 #include <limits>
+#include <thread>
 #include <vector>
 
 namespace {
@@ -105,8 +106,12 @@ extern "C" int shard_plan_throughput(const shard_plan_problem* p, int32_t with_r
     std::vector<Back> back(g.size(), Back{-1, -1});
     for (int c = 1; c <= N; ++c)
         if (pr[c] <= p->mem_bytes[0]) g[idx(c, 1, 0)] = range_comp(0, c, 0);
-    for (int c = 1; c < N; ++c)
-        for (size_t set = 1; set < S; set += 2)  // device 0 is always in the set
+    // Relaxations out of the states with c layers placed.  A state (c, set, k) only writes states
+    // (c2 > c, set + {j}, j) with j outside set, so for one c different sets never write the same
+    // entry: the sets are dealt out to host threads, each set's k loop stays in one thread, and
+    // the result does not depend on the number of threads.
+    auto relax = [&](int c, size_t set_lo, size_t set_hi) {
+        for (size_t set = set_lo | 1; set < set_hi; set += 2)  // device 0 is always in the set
             for (int k = 0; k < M; ++k) {
                 const double cur = g[idx(c, set, k)];
                 if (cur == INF) continue;
@@ -124,6 +129,20 @@ extern "C" int shard_plan_throughput(const shard_plan_problem* p, int32_t with_r
                     }
                 }
             }
+    };
+    unsigned n_threads = std::thread::hardware_concurrency();
+    if (n_threads > 16) n_threads = 16;
+    if (n_threads < 1 || S < 4096) n_threads = 1;   // small problems: not worth a thread
+    for (int c = 1; c < N; ++c) {
+        if (n_threads == 1) { relax(c, 0, S); continue; }
+        std::vector<std::thread> pool;
+        const size_t chunk = (S / n_threads + 1) & ~static_cast<size_t>(1);   // even boundaries
+        for (unsigned t = 0; t < n_threads; ++t) {
+            const size_t lo = t * chunk, hi = t + 1 == n_threads ? S : (t + 1) * chunk;
+            if (lo < S) pool.emplace_back(relax, c, lo, hi < S ? hi : S);
+        }
+        for (auto& th : pool) th.join();
+    }
     double best = INF;
     size_t bset = 0;
     int bk = -1;

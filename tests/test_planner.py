@@ -88,6 +88,33 @@ def test_throughput_dp_matches_enumeration(lib, n, m, seed, mem, hop):
         assert len(runs) == len(set(runs))
 
 
+@pytest.mark.parametrize("seed", [11, 12])
+def test_throughput_dp_on_many_devices_equals_the_problem_without_the_useless_ones(lib, seed):
+    """13 devices (8192 subsets: the size from which the dynamic program deals the subsets out
+    to host threads), nine of them without memory for a single layer: the optimum is that of
+    the four usable devices alone, which the enumeration above covers, and the plan uses only
+    those."""
+    small = problem(9, 4, seed, mem=6.0, bw_scale=1.0)
+    keep = [0, 5, 7, 12]                      # where the four usable devices sit in the big problem
+    m = 13
+    rng = np.random.default_rng(100 + seed)
+    big = dict(t_comp=rng.uniform(0.01, 0.02, (9, m)),     # the useless devices would be much faster
+               act_bytes=small["act_bytes"], req_bytes=small["req_bytes"],
+               mem_bytes=np.zeros(m), bandwidth=rng.uniform(50.0, 60.0, (m, m)))
+    for a, ka in enumerate(keep):
+        big["t_comp"][:, ka] = small["t_comp"][:, a]
+        big["mem_bytes"][ka] = small["mem_bytes"][a]
+        for b, kb in enumerate(keep):
+            big["bandwidth"][ka, kb] = small["bandwidth"][a, b]
+    for hop in (False, True):
+        want, _ = orc.best_throughput(small, hop)
+        t_small, _ = lib.plan_throughput(small, hop)
+        t_big, dev = lib.plan_throughput(big, hop)
+        assert t_small == pytest.approx(want, rel=1e-12)
+        assert t_big == pytest.approx(want, rel=1e-12)
+        assert set(dev) <= set(keep) and dev[0] == 0
+
+
 def test_paper_baselines_are_special_cases(lib):
     """Edge-Solo is the plan with one device; Cloud-Edge-Opt the plan with two; the planner
     over the full pool is never worse than either (Sec. 5.1 "Baselines", Sec. 5.2)."""
