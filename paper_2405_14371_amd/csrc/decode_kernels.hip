@@ -3,6 +3,8 @@
 // 16-byte loads per lane, many independent loads in flight, fixed-order reductions.
 #include "kernels.hpp"
 
+#include <mutex>
+
 namespace shk {
 
 // ---------------------------------------------------------------------------------------
@@ -474,12 +476,11 @@ template <int TILES, int STAGES>
 static void launch_dl_dma(const DecodeLinear& a, const SeqBatch& sb, dim3 grid, int rows, hipStream_t st) {
     constexpr size_t lds = static_cast<size_t>(STAGES) * (16 * TILES + 16) * 512;
     static_assert(lds <= 160 * 1024, "LDS of a compute unit");
-    static bool prepared = false;  // more than 64 KB of LDS per workgroup is an opt-in
-    if (!prepared) {
+    static std::once_flag once;  // more than 64 KB of LDS per workgroup is an opt-in
+    std::call_once(once, [] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(decode_linear_dma_kernel<TILES, STAGES>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        prepared = true;
-    }
+    });
     launch((decode_linear_dma_kernel<TILES, STAGES>), grid, dim3(512), lds, st, a, sb, rows);
 }
 

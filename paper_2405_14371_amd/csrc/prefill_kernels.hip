@@ -4,6 +4,8 @@
 // softmax statistics kept per lane and merged with one wavefront shuffle.
 #include "kernels.hpp"
 
+#include <mutex>
+
 namespace shk {
 
 // ---------------------------------------------------------------------------------------
@@ -268,12 +270,11 @@ static void launch_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st
     const int total = tiles_m * tiles_n;
     const int grid = ((total + 7) / 8) * 8;
     constexpr size_t lds = 2u * (BN + BM) * PITCH * sizeof(float);
-    static bool prepared = false;  // more than 64 KB of LDS per workgroup is an opt-in
-    if (!prepared) {
+    static std::once_flag once;  // more than 64 KB of LDS per workgroup is an opt-in
+    std::call_once(once, [] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<T, BN, BM, ROWDW, PITCH>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        prepared = true;
-    }
+    });
     launch((gemm_kernel<T, BN, BM, ROWDW, PITCH>), dim3(grid), dim3(256), lds, st, a, sb, tiles_m, total);
 }
 
@@ -415,12 +416,11 @@ static void launch_gemm_dma(const PrefillGemm& a, const SeqBatch& sb, hipStream_
     const int grid = ((total + 7) / 8) * 8;
     constexpr size_t lds = static_cast<size_t>(STAGES) * (BN + BM) * ROWDW * sizeof(float);
     static_assert(lds <= 160 * 1024, "LDS of a compute unit");
-    static bool prepared = false;
-    if (!prepared) {
+    static std::once_flag once;  // more than 64 KB of LDS per workgroup is an opt-in
+    std::call_once(once, [] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_dma_kernel<T, BN, BM, ROWDW, STAGES, WN, WM>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        prepared = true;
-    }
+    });
     launch(gemm_dma_kernel<T, BN, BM, ROWDW, STAGES, WN, WM>, dim3(grid, a.kslices > 1 ? a.kslices : 1), dim3(64 * WN * WM), lds,
            st, a, sb, tiles_m, total);
 }
@@ -1083,12 +1083,11 @@ static void launch_pa_lds_q(const PrefillAttn& a, const SeqBatch& sb, hipStream_
     static_assert(lds <= 160 * 1024, "LDS of a compute unit");
     static_assert(KS == 1 || static_cast<size_t>(KS) * STAGES * 2 * 32 * DH * sizeof(KT) >= QT * (DH / 32 * 16 + 2) * 64 * 4,
                   "the merge buffer lives in the ring");
-    static bool prepared = false;
-    if (!prepared) {
+    static std::once_flag once;  // more than 64 KB of LDS per workgroup is an opt-in
+    std::call_once(once, [] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_attn_lds_kernel<KT, DH, KS, STAGES, QT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        prepared = true;
-    }
+    });
     const dim3 grid((a.T + 32 * QT - 1) / (32 * QT), a.hq, a.B);
     launch(prefill_attn_lds_kernel<KT, DH, KS, STAGES, QT>, grid, dim3(64 * QT * KS), lds, st, a, sb);
 }
