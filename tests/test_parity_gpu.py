@@ -286,7 +286,9 @@ def test_runtime_errors_leave_state_unchanged(lib):
     expect(lib.SHARD_E_STATE, sh.prefill, [a, a], 2, x, y)          # duplicate id
     expect(lib.SHARD_E_STATE, sh.prefill, [1], 2, x, y)             # slot 1 not live
     expect(lib.SHARD_E_KV_FULL, sh.prefill, [a], 17, x, y)          # longer than max_seq_len...
-    expect(lib.SHARD_E_INVAL, sh.prefill, [a], 0, x, y)
+    expect(lib.SHARD_E_INVAL, sh.prefill, [a], 0, x, y)                # no tokens
+    expect(lib.SHARD_E_INVAL, sh.prefill, [], 4, x, y)                 # no sequences
+    expect(lib.SHARD_E_INVAL, sh.decode, [], x, y)
     expect(lib.SHARD_E_INVAL, sh.prefill, [a], 4, None, y)
     assert sh.seq_len(a) == 0
     sh.prefill([a], 12, x, y)
