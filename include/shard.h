@@ -25,6 +25,16 @@
  *    host memory.  The library never takes ownership of caller memory.
  *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream).  Work is
  *    enqueued on it and the call returns without waiting; the caller synchronises.
+ *  - State: a call that fails - at validation or at a kernel launch - leaves the sequences'
+ *    lengths and pages as they were before it.
+ *  - Range of the 16-bit path (weight_dtype SHARD_BF16): activations fed to the matrix cores
+ *    (the half copy of the residual stream, the SwiGLU output) and the KV cache are IEEE half,
+ *    largest finite value 65504.  Every kernel that rounds such a value to half tests it; a
+ *    value beyond the range (or a NaN) raises a sticky flag in host-visible memory, and from
+ *    then on shard_prefill / shard_decode return SHARD_E_RANGE before
+ *    they launch anything (the flag is seen once the offending kernel has run, so at the
+ *    latest by the call after the caller's next synchronisation).  shard_overflow reads and
+ *    optionally clears it.  The fp32 path has no such limit.
  *  - A shard handle is not thread-safe; use one thread per handle at a time.
  *  - Several streams: calls issued (from that one thread) on different streams may overlap on
  *    the device when they carry different sequences - micro-batches of a pipeline stage, for
@@ -51,7 +61,8 @@ enum {
     SHARD_E_NOMEM = -2,   /* device or host allocation failed */
     SHARD_E_KV_FULL = -3, /* sequence would exceed max_seq_len, or no free sequence slot */
     SHARD_E_STATE = -4,   /* unknown seq_id, decode on an empty sequence, duplicate seq_id */
-    SHARD_E_HIP = -5      /* a HIP runtime call failed */
+    SHARD_E_HIP = -5,     /* a HIP runtime call failed */
+    SHARD_E_RANGE = -6    /* a 16-bit activation or cache value left the range of IEEE half */
 };
 
 enum { SHARD_F32 = 0, SHARD_BF16 = 1 };
@@ -157,6 +168,12 @@ int shard_prefill(shard_t *s, const int32_t *seq_ids, int32_t B, int32_t T,
 int shard_decode(shard_t *s, const int32_t *seq_ids, int32_t B,
                  const void *x_in, void *x_out, void *hip_stream);
 
+/* Whether a value rounded to IEEE half by this shard's kernels has left half's range since
+ * the shard was created (or since the flag was last cleared): *overflowed = 0 or 1, for the
+ * work that has completed on the device.  clear != 0 resets the flag; the KV cache of the
+ * sequences that were running may hold infinities - free them.  Always 0 for SHARD_F32. */
+int shard_overflow(shard_t *s, int32_t clear, int32_t *overflowed);
+
 /* Offline profiling of this device's column of the planner's inputs (Sec. 3 "Profiling"):
  * on scratch sequences and zero-free synthetic activations, time every layer of the range
  * with HIP events in a prefill of (B, T_prefill) and in n_decode following decode steps,
@@ -191,9 +208,9 @@ int shard_timing_enable(shard_t *s, int32_t on);
 int shard_timing_read(shard_t *s, int64_t launches[SHARD_K_COUNT], double seconds[SHARD_K_COUNT]);
 
 /* ---- The ends of a model around its decoder layers -------------------------------------
- * The paper counts "an embedding layer, multiple decoder layers and an output layer" among
- * the N layers it places (Sec. 4 "System Model") and pins the first of them, which sees the
- * raw input tokens, to the source node (Eq. 4).  A shard maps hidden states to hidden
+ * The N layers the paper places include the token embedding and the output projection next
+ * to the decoder layers (Sec. 4 "System Model"), and the first of them, which sees the raw
+ * input tokens, is pinned to the source node (Eq. 4).  A shard maps hidden states to hidden
  * states; these entry points supply what comes before the first shard and after the last:
  * the token embedding lookup, and the final RMSNorm + output projection ("LM head") with a
  * greedy choice of the next token, so that a whole token loop can run on library calls.

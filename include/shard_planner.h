@@ -36,7 +36,7 @@ typedef struct {
  * carries the memory its own best path has used on every device, and a transition is
  * allowed only if layer i still fits (Eq. 5 along that path).
  * device_of_layer: host array [N] (out).  Returns 0, -1 on bad arguments, -2 when no
- * feasible assignment was found. */
+ * feasible assignment was found, -3 when a host allocation failed. */
 int shard_plan_latency(const shard_plan_problem *p, int32_t *device_of_layer, double *t_total);
 
 /* Pipeline-parallel inference (Sec. 4.2): every selected device gets ONE contiguous range
@@ -45,9 +45,35 @@ int shard_plan_latency(const shard_plan_problem *p, int32_t *device_of_layer, do
  * Algo. 2 over (layers placed, device set, last device).  Exact for this formulation,
  * memory limits included (Eq. 12).  with_return_hop != 0 also counts the transfer of the
  * last activation back to device 0 as a stage.
- * Returns 0, -1 on bad arguments (or M > 16), -2 when nothing fits. */
+ * Returns 0, -1 on bad arguments (or M > 16), -2 when nothing fits, -3 when a host
+ * allocation or thread start failed. */
 int shard_plan_throughput(const shard_plan_problem *p, int32_t with_return_hop,
                           int32_t *device_of_layer, double *t_slowest_stage);
+
+/* From a plan to the pipeline it describes (Sec. 4.2): the devices of a throughput plan, in
+ * layer order, are the stages; a stage's compute time is the sum of its layers' times on its
+ * device (the t_comp term of Eq. 9), and the link between two consecutive stages carries the
+ * output activation of the earlier stage's last layer, O_i / B_{k,j} (Eq. 1; the t_comm term of
+ * Eq. 9); the generated token returns from the last stage's device to the first's over
+ * O_{N-1} / B (zero when they are the same device).  These are the inputs of
+ * shard_simulate_pipeline (shard_schedule.h).
+ *   device_of_layer   [N]     a plan in which every device owns ONE contiguous range
+ *   t_prefill, t_decode [N][M] seconds of layer i on device j in the prefill / in one decode
+ *                             iteration (the two columns shard_profile measures)
+ *   act_prefill, act_decode [N] bytes of layer i's output activation in the two phases
+ *   bandwidth         [M][M]  bytes per second
+ * Outputs (host arrays of N entries each, of which the first *n_stages are written):
+ * stage_device, t_stage_prefill, t_stage_decode; c_prefill and c_decode hold *n_stages - 1
+ * link times; *c_return the return hop.
+ * Returns 0; -1 on bad arguments (NULL, sizes, a device index outside [0, M), a bandwidth
+ * that is not positive on a link the plan uses); -2 when a device owns two separate ranges
+ * (legal for the latency plan of Sec. 4.1, but not a pipeline). */
+int shard_plan_to_stages(int32_t n_layers, int32_t n_devices, const int32_t *device_of_layer,
+                         const double *t_prefill, const double *t_decode,
+                         const double *act_prefill, const double *act_decode, const double *bandwidth,
+                         int32_t *n_stages, int32_t *stage_device,
+                         double *t_stage_prefill, double *t_stage_decode,
+                         double *c_prefill, double *c_decode, double *c_return);
 
 #ifdef __cplusplus
 }

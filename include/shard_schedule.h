@@ -43,7 +43,8 @@ typedef struct {
  * busy_s (out, host array [S], may be NULL): seconds each stage spent computing.
  * Tokens produced: MB * (1 + n_decode) per sequence of a micro-batch; throughput is that
  * count times the micro-batch size divided by the makespan.
- * Returns 0, or -1 on bad arguments (NULL, sizes out of range, negative or non-finite times). */
+ * Returns 0, -1 on bad arguments (NULL, sizes out of range, negative or non-finite times), or
+ * -3 when a host allocation failed. */
 int shard_simulate_pipeline(const shard_pipeline_problem *p, int32_t no_bubbles,
                             double *makespan_s, double *busy_s);
 

@@ -33,6 +33,8 @@ cache is a plain [position, kv_head, dh] array per layer and sequence.
 
 The ends of a model (embed, logits, greedy) are at the bottom of the file.
 
+The two error metrics (max_rel_err, max_rel_err_strict) are pinned by hand-computed values.
+
 Parity status of this file: every function is pinned by tests/test_oracle_pins.py
 (pure-Python brute force on tiny shapes, closed forms, invariants, independent library
 routines).  Unpinned: agreement of the RoPE pairing convention with real Llama 2
@@ -194,3 +196,13 @@ def max_rel_err(y: np.ndarray, y_ref: np.ndarray) -> float:
     of zero-mean data.)"""
     y, y_ref = np.asarray(y, F64), np.asarray(y_ref, F64)
     return float(np.max(np.abs(y - y_ref)) / np.max(np.abs(y_ref)))
+
+
+def max_rel_err_strict(y: np.ndarray, y_ref: np.ndarray) -> float:
+    """The stricter companion of max_rel_err: every element's deviation over its own
+    reference magnitude, but never over less than the root-mean-square of the reference
+    tensor (so that elements near a zero crossing are measured against the data's scale,
+    not against themselves)."""
+    y, y_ref = np.asarray(y, F64), np.asarray(y_ref, F64)
+    rms = np.sqrt(np.mean(y_ref * y_ref))
+    return float(np.max(np.abs(y - y_ref) / np.maximum(np.abs(y_ref), rms)))

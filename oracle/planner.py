@@ -14,7 +14,8 @@ first range on device 0; a stage costs max(compute of its range, receiving its i
 (Eq. 9); minimise the slowest stage (Eq. 10) subject to Eq. 12.
 
 Pinned by tests/test_planner.py: hand-computed two-layer examples, single-device and
-infinite / zero-bandwidth closed forms.
+infinite / zero-bandwidth closed forms; stages_of by a hand-worked five-layer plan and by the
+identity max(stage compute, incoming link) = stage_time_of.
 """
 from __future__ import annotations
 
@@ -94,3 +95,27 @@ def best_throughput(prob, with_return_hop=False):
                 if t < best:
                     best, arg = t, tuple(dev)
     return best, arg
+
+
+def stages_of(dev, t_prefill, t_decode, act_prefill, act_decode, bandwidth):
+    """The pipeline a contiguous-range plan describes (Sec. 4.2): per stage the sum of its
+    layers' times on its device (the compute term of Eq. 9), per boundary the time O_i / B of
+    the activation that crosses it (Eq. 1), and the return of the last activation to the first
+    stage's device.  Written stage by stage from the definition: list the maximal runs of equal
+    devices, then read each quantity off the run."""
+    runs = []                                   # (device, first layer, one past the last layer)
+    for i, d in enumerate(dev):
+        if runs and runs[-1][0] == d:
+            runs[-1] = (d, runs[-1][1], i + 1)
+        else:
+            runs.append((d, i, i + 1))
+    devices = [r[0] for r in runs]
+    if len(set(devices)) != len(devices):
+        raise ValueError("a device owns two separate ranges")
+    tp = [sum(t_prefill[l][d] for l in range(lo, hi)) for d, lo, hi in runs]
+    td = [sum(t_decode[l][d] for l in range(lo, hi)) for d, lo, hi in runs]
+    cp = [act_prefill[a[2] - 1] / bandwidth[a[0]][b[0]] for a, b in zip(runs[:-1], runs[1:])]
+    cd = [act_decode[a[2] - 1] / bandwidth[a[0]][b[0]] for a, b in zip(runs[:-1], runs[1:])]
+    last = len(dev) - 1
+    c_ret = 0.0 if devices[-1] == devices[0] else act_decode[last] / bandwidth[devices[-1]][devices[0]]
+    return dict(stages=devices, t_prefill=tp, t_decode=td, c_prefill=cp, c_decode=cd, c_return=c_ret)

@@ -11,7 +11,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libshard.so")
 
-SHARD_OK, SHARD_E_INVAL, SHARD_E_NOMEM, SHARD_E_KV_FULL, SHARD_E_STATE, SHARD_E_HIP = 0, -1, -2, -3, -4, -5
+SHARD_OK, SHARD_E_INVAL, SHARD_E_NOMEM, SHARD_E_KV_FULL, SHARD_E_STATE, SHARD_E_HIP, SHARD_E_RANGE = 0, -1, -2, -3, -4, -5, -6
 SHARD_F32, SHARD_BF16 = 0, 1
 SHARD_MAX_BATCH = 64
 KERNEL_CLASSES = ("decode_qkv", "decode_attn", "decode_o", "decode_gateup", "decode_down", "prefill_norm",
@@ -33,10 +33,13 @@ class PipelineProblem(C.Structure):
 
 EXPORTS = (
     "shard_create", "shard_destroy", "shard_seq_alloc", "shard_seq_free", "shard_seq_len",
-    "shard_prefill", "shard_decode", "shard_profile", "shard_timing_enable", "shard_timing_read",
-    "shard_last_error", "shard_plan_latency", "shard_plan_throughput", "shard_simulate_pipeline",
+    "shard_prefill", "shard_decode", "shard_overflow", "shard_profile",
+    "shard_timing_enable", "shard_timing_read",
+    "shard_last_error", "shard_plan_latency", "shard_plan_throughput", "shard_plan_to_stages", "shard_simulate_pipeline",
     "shard_ends_create", "shard_ends_destroy", "shard_ends_embed", "shard_ends_logits", "shard_ends_argmax",
+    "shard_variant_name", "shard_variant_prefill_gemm", "shard_variant_decode_linear", "shard_test_inject_launch_error",
 )
+FAMILY_PREFILL_GEMM, FAMILY_DECODE_STREAM, FAMILY_DECODE_MFMA = 0, 1, 2
 
 
 class ModelCfg(C.Structure):
@@ -91,21 +94,31 @@ def load():
     lib.shard_seq_len.argtypes = [vp, i32]
     lib.shard_prefill.argtypes = [vp, C.POINTER(i32), i32, i32, vp, vp, vp]
     lib.shard_decode.argtypes = [vp, C.POINTER(i32), i32, vp, vp, vp]
+    lib.shard_overflow.argtypes = [vp, i32, C.POINTER(i32)]
     lib.shard_profile.argtypes = [vp, i32, i32, i32, i32, C.POINTER(LayerProfile)]
     lib.shard_timing_enable.argtypes = [vp, i32]
     lib.shard_timing_read.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double)]
     lib.shard_plan_latency.argtypes = [C.POINTER(PlanProblem), C.POINTER(i32), C.POINTER(C.c_double)]
     lib.shard_plan_throughput.argtypes = [C.POINTER(PlanProblem), i32, C.POINTER(i32), C.POINTER(C.c_double)]
+    dp = C.POINTER(C.c_double)
+    lib.shard_plan_to_stages.argtypes = [i32, i32, C.POINTER(i32), dp, dp, dp, dp, dp, C.POINTER(i32), C.POINTER(i32),
+                                         dp, dp, dp, dp, dp]
     lib.shard_simulate_pipeline.argtypes = [C.POINTER(PipelineProblem), i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.shard_ends_create.argtypes = [C.POINTER(vp), C.POINTER(ModelCfg), i32, i32, vp, vp, vp, i32]
     lib.shard_ends_destroy.argtypes = [vp]
     lib.shard_ends_embed.argtypes = [vp, C.POINTER(i32), i32, vp, vp]
     lib.shard_ends_logits.argtypes = [vp, vp, i32, vp, vp]
     lib.shard_ends_argmax.argtypes = [vp, vp, i32, vp, vp]
+    lib.shard_variant_name.argtypes = [i32, i32]
+    lib.shard_variant_name.restype = C.c_char_p
+    lib.shard_variant_prefill_gemm.argtypes = [i32, i32, i32, i32, i32, C.POINTER(i32)]
+    lib.shard_variant_decode_linear.argtypes = [C.POINTER(ModelCfg), i32, i32, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
+    lib.shard_test_inject_launch_error.argtypes = [i32]
+    lib.shard_test_inject_launch_error.restype = None
     lib.shard_last_error.argtypes = []
     lib.shard_last_error.restype = C.c_char_p
     for name in EXPORTS:
-        if name != "shard_last_error":
+        if name not in ("shard_last_error", "shard_variant_name", "shard_test_inject_launch_error"):
             getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -201,6 +214,11 @@ class Shard:
         ids, n = _ids(seq_ids)
         _check(load().shard_decode(self._h, ids, n, _ptr(x_in), _ptr(x_out), stream))
 
+    def overflow(self, clear: bool = False) -> bool:
+        out = C.c_int32(0)
+        _check(load().shard_overflow(self._h, 1 if clear else 0, C.byref(out)))
+        return bool(out.value)
+
     def profile(self, B: int, T_prefill: int, n_decode: int, iters: int = 3) -> list:
         out = (LayerProfile * self.n_layers)()
         _check(load().shard_profile(self._h, B, T_prefill, n_decode, iters, out))
@@ -266,6 +284,36 @@ def pack_layers(layers: list, weight_dtype: int) -> list:
     return out
 
 
+def variant_names(family: int) -> list:
+    """All variant names of a family, in table order."""
+    out, i = [], 0
+    while True:
+        name = load().shard_variant_name(family, i)
+        if name is None:
+            return out
+        out.append(name.decode())
+        i += 1
+
+
+def variant_prefill_gemm(weight_dtype: int, M: int, N: int, K: int, residual_epilogue: bool):
+    """shard_variant_prefill_gemm: (variant name, K slices)."""
+    ks = C.c_int32(0)
+    i = _check(load().shard_variant_prefill_gemm(weight_dtype, M, N, K, 1 if residual_epilogue else 0, C.byref(ks)))
+    return load().shard_variant_name(FAMILY_PREFILL_GEMM, i).decode(), ks.value
+
+
+def variant_decode_linear(cfg: dict, weight_dtype: int, B: int, N: int, K: int):
+    """shard_variant_decode_linear: (variant name, rows per pass, weight rows per workgroup)."""
+    mc = model_cfg(cfg, weight_dtype)
+    fam, rpp, rows = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    i = _check(load().shard_variant_decode_linear(C.byref(mc), B, N, K, C.byref(fam), C.byref(rpp), C.byref(rows)))
+    return load().shard_variant_name(fam.value, i).decode(), rpp.value, rows.value
+
+
+def inject_launch_error(on: bool) -> None:
+    load().shard_test_inject_launch_error(1 if on else 0)
+
+
 def _plan_problem(prob: dict):
     dbl = lambda a: np.ascontiguousarray(a, dtype=np.float64)
     arrs = [dbl(prob[k]) for k in ("t_comp", "act_bytes", "req_bytes", "mem_bytes", "bandwidth")]
@@ -312,19 +360,22 @@ def simulate_pipeline(t_prefill, t_decode, c_prefill, c_decode, c_return, n_micr
 
 
 def stages_of_plan(device_of_layer, t_prefill_layer, t_decode_layer, act_bytes_prefill, act_bytes_decode, bandwidth):
-    """Collapse a throughput plan (one contiguous layer range per device) into the per-stage
-    times and link times shard_simulate_pipeline takes.  Per-layer times are [N][M] (layer,
-    device), activation sizes [N], bandwidth [M][M] in bytes per second."""
-    dev = list(device_of_layer)
-    stages = [d for i, d in enumerate(dev) if i == 0 or dev[i - 1] != d]
-    tp, td, cp, cd = [], [], [], []
-    for d in stages:
-        idx = [i for i, x in enumerate(dev) if x == d]
-        tp.append(float(sum(t_prefill_layer[i][d] for i in idx)))
-        td.append(float(sum(t_decode_layer[i][d] for i in idx)))
-    for a, b in zip(stages[:-1], stages[1:]):
-        last = max(i for i, x in enumerate(dev) if x == a)
-        cp.append(float(act_bytes_prefill[last]) / float(bandwidth[a][b]))
-        cd.append(float(act_bytes_decode[last]) / float(bandwidth[a][b]))
-    c_ret = 0.0 if stages[-1] == stages[0] else float(act_bytes_decode[len(dev) - 1]) / float(bandwidth[stages[-1]][stages[0]])
-    return dict(stages=stages, t_prefill=tp, t_decode=td, c_prefill=cp, c_decode=cd, c_return=c_ret)
+    """shard_plan_to_stages: collapse a throughput plan (one contiguous layer range per device)
+    into the per-stage and per-link times shard_simulate_pipeline takes.  Per-layer times are
+    [N][M] (layer, device), activation sizes [N], bandwidth [M][M] in bytes per second."""
+    dbl = lambda a: np.ascontiguousarray(a, dtype=np.float64)
+    ptr = lambda a: a.ctypes.data_as(C.POINTER(C.c_double))
+    tp, td, ap, ad, bw = (dbl(a) for a in (t_prefill_layer, t_decode_layer, act_bytes_prefill, act_bytes_decode, bandwidth))
+    n, m = tp.shape
+    dev = (C.c_int32 * n)(*[int(d) for d in device_of_layer])
+    n_stages = C.c_int32(0)
+    stage_dev = (C.c_int32 * n)()
+    out = [np.zeros(n, dtype=np.float64) for _ in range(4)]
+    c_ret = C.c_double(0.0)
+    rc = load().shard_plan_to_stages(n, m, dev, ptr(tp), ptr(td), ptr(ap), ptr(ad), ptr(bw), C.byref(n_stages), stage_dev,
+                                     ptr(out[0]), ptr(out[1]), ptr(out[2]), ptr(out[3]), C.byref(c_ret))
+    if rc:
+        raise ShardError(rc, "a device owns two separate layer ranges" if rc == -2 else "bad plan arguments")
+    S = n_stages.value
+    return dict(stages=list(stage_dev)[:S], t_prefill=out[0][:S].tolist(), t_decode=out[1][:S].tolist(),
+                c_prefill=out[2][:S - 1].tolist(), c_decode=out[3][:S - 1].tolist(), c_return=c_ret.value)

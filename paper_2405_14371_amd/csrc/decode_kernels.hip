@@ -3,6 +3,7 @@
 // 16-byte loads per lane, many independent loads in flight, fixed-order reductions.
 #include "kernels.hpp"
 
+#include <atomic>
 #include <mutex>
 
 namespace shk {
@@ -170,8 +171,8 @@ __global__ __launch_bounds__(256) void decode_linear_kernel(DecodeLinear a, SeqB
         const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
         typedef typename ActOf<WT>::type CT;  // cache element type
         CT* kp = static_cast<CT*>(a.kv.k);
-        kp[at] = Elem<CT>::from_f32(r0);
-        kp[at + 1] = Elem<CT>::from_f32(r1);
+        kp[at] = store_cast<CT>(r0, a.oflow);
+        kp[at + 1] = store_cast<CT>(r1, a.oflow);
         return;
     }
     {
@@ -179,8 +180,8 @@ __global__ __launch_bounds__(256) void decode_linear_kernel(DecodeLinear a, SeqB
         const int hk = (n0 - nq - nk) / dh, e = n0 % dh;
         const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
         CT* vp = static_cast<CT*>(a.kv.v);
-        vp[at] = Elem<CT>::from_f32(v0);
-        vp[at + 1] = Elem<CT>::from_f32(v1);
+        vp[at] = store_cast<CT>(v0, a.oflow);
+        vp[at + 1] = store_cast<CT>(v1, a.oflow);
     }
 }
 
@@ -192,18 +193,38 @@ static void launch_dl(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st)
 
 // (rows per workgroup, chunks in flight) from a sweep on MI355X over the Llama2 shapes:
 // many small workgroups win; wide matrices like more rows per workgroup, bf16 rows
-// (half the bytes) like more rows still.
+// (half the bytes) like more rows still.  The choice is a pure host function of the shape
+// (choose_decode_linear), so that tests can ask which variant a shape lands on.
+enum DlId { DL_NB1_WIDE, DL_NB1_LONGK, DL_NB1_SQUARE, DL_NB2, DL_NB4, DL_NB8, DL_ID_COUNT };
+static const char* const DL_NAMES[2][DL_ID_COUNT] = {
+    {"f32 stream nb1 r4 u1 (N >= 8192)", "f32 stream nb1 r4 u2 rot (K > 8192)", "f32 stream nb1 r2 u4", "f32 stream nb2 r4 u2",
+     "f32 stream nb4 r4 u2", "f32 stream nb8 r4 u1"},
+    {"f16 stream nb1 r8 u1 (N >= 8192)", "f16 stream nb1 r4 u2 rot (K > 8192)", "f16 stream nb1 r4 u1", "f16 stream nb2 r4 u2",
+     "f16 stream nb4 r4 u2", "f16 stream nb8 r4 u1"}};
+const char* decode_linear_variant_name(int id) {
+    return id >= 0 && id < 2 * DL_ID_COUNT ? DL_NAMES[id / DL_ID_COUNT][id % DL_ID_COUNT] : nullptr;
+}
+// index into the name table: DL_ID_COUNT * (16-bit weights) + DlId
+int choose_decode_linear(int wt, int nb, int N, int K) {
+    int id;
+    if (nb == 1) id = N >= 8192 ? DL_NB1_WIDE : (K > 8192 ? DL_NB1_LONGK : DL_NB1_SQUARE);
+    else if (nb == 2) id = DL_NB2;
+    else if (nb <= 4) id = DL_NB4;
+    else id = DL_NB8;
+    return (wt == DT_F32 ? 0 : DL_ID_COUNT) + id;
+}
+
 template <typename WT>
 static void launch_dl_t(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
     constexpr bool f32 = sizeof(WT) == 4;
-    if (a.nb == 1) {
-        if (a.N >= 8192) { if (f32) launch_dl<WT, 1, 4, 1>(a, sb, st); else launch_dl<WT, 1, 8, 1>(a, sb, st); }
-        else if (a.K > 8192) { if (f32) launch_dl<WT, 1, 4, 2, true>(a, sb, st); else launch_dl<WT, 1, 4, 2, true>(a, sb, st); }
-        else { if (f32) launch_dl<WT, 1, 2, 4>(a, sb, st); else launch_dl<WT, 1, 4, 1>(a, sb, st); }
+    switch (choose_decode_linear(a.wt, a.nb, a.N, a.K) % DL_ID_COUNT) {
+        case DL_NB1_WIDE: if (f32) launch_dl<WT, 1, 4, 1>(a, sb, st); else launch_dl<WT, 1, 8, 1>(a, sb, st); break;
+        case DL_NB1_LONGK: launch_dl<WT, 1, 4, 2, true>(a, sb, st); break;
+        case DL_NB1_SQUARE: if (f32) launch_dl<WT, 1, 2, 4>(a, sb, st); else launch_dl<WT, 1, 4, 1>(a, sb, st); break;
+        case DL_NB2: launch_dl<WT, 2, 4, 2>(a, sb, st); break;
+        case DL_NB4: launch_dl<WT, 4, 4, 2>(a, sb, st); break;
+        default: launch_dl<WT, 8, 4, 1>(a, sb, st); break;
     }
-    else if (a.nb == 2) launch_dl<WT, 2, 4, 2>(a, sb, st);
-    else if (a.nb <= 4) launch_dl<WT, 4, 4, 2>(a, sb, st);
-    else launch_dl<WT, 8, 4, 1>(a, sb, st);
 }
 
 void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
@@ -269,7 +290,7 @@ __device__ __forceinline__ void mfma_linear_finish(const DecodeLinear& a, const 
                 const size_t at = static_cast<size_t>(b) * a.N + n;
                 const float y = a.resid[at] + s_val[r * 16 + b];
                 a.out[at] = y;
-                if (a.out_h) static_cast<f16_t*>(a.out_h)[at] = static_cast<f16_t>(y);
+                if (a.out_h) static_cast<f16_t*>(a.out_h)[at] = store_cast<f16_t>(y, a.oflow);
             }
         }
         return;
@@ -282,7 +303,7 @@ __device__ __forceinline__ void mfma_linear_finish(const DecodeLinear& a, const 
         const float v0 = s_val[(2 * j) * 16 + b], v1 = s_val[(2 * j + 1) * 16 + b];
         if (a.epi == EPI_SWIGLU) {
             const int F = a.N / 2;
-            static_cast<f16_t*>(a.out_b)[static_cast<size_t>(b) * F + n0 / 2] = static_cast<f16_t>(v0 / (1.0f + expf(-v0)) * v1);
+            static_cast<f16_t*>(a.out_b)[static_cast<size_t>(b) * F + n0 / 2] = store_cast<f16_t>(v0 / (1.0f + expf(-v0)) * v1, a.oflow);
             continue;
         }
         const int dh = a.kv.dh, nq = a.hq * dh, nk = a.kv.hkv * dh;
@@ -299,15 +320,15 @@ __device__ __forceinline__ void mfma_linear_finish(const DecodeLinear& a, const 
             const int hk = (n0 - nq) / dh;
             const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
             f16_t* kp = static_cast<f16_t*>(a.kv.k);
-            kp[at] = static_cast<f16_t>(r0);
-            kp[at + 1] = static_cast<f16_t>(r1);
+            kp[at] = store_cast<f16_t>(r0, a.oflow);
+            kp[at + 1] = store_cast<f16_t>(r1, a.oflow);
             continue;
         }
         const int hk = (n0 - nq - nk) / dh;
         const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
         f16_t* vp = static_cast<f16_t*>(a.kv.v);
-        vp[at] = static_cast<f16_t>(v0);
-        vp[at + 1] = static_cast<f16_t>(v1);
+        vp[at] = store_cast<f16_t>(v0, a.oflow);
+        vp[at + 1] = store_cast<f16_t>(v1, a.oflow);
     }
 }
 
@@ -478,44 +499,57 @@ static void launch_dl_dma(const DecodeLinear& a, const SeqBatch& sb, dim3 grid, 
     static_assert(lds <= 160 * 1024, "LDS of a compute unit");
     static std::once_flag once;  // more than 64 KB of LDS per workgroup is an opt-in
     std::call_once(once, [] {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(decode_linear_dma_kernel<TILES, STAGES>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        note_kernel_attribute(hipFuncSetAttribute(reinterpret_cast<const void*>(decode_linear_dma_kernel<TILES, STAGES>),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
     });
     launch((decode_linear_dma_kernel<TILES, STAGES>), grid, dim3(512), lds, st, a, sb, rows);
 }
 
-void launch_decode_linear_mfma(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
+// Variant and rows per workgroup of the matrix-core projection for an [N, K] matrix: ids 0..3 are
+// the LDS-ring kernel with 1..4 row tiles, ids 4..11 the register kernel with 1..8 row tiles.
+static const char* const DLM_NAMES[12] = {
+    "f16 mfma lds-ring 1 tile", "f16 mfma lds-ring 2 tiles", "f16 mfma lds-ring 3 tiles", "f16 mfma lds-ring 4 tiles",
+    "f16 mfma reg 1 tile", "f16 mfma reg 2 tiles", "f16 mfma reg 3 tiles", "f16 mfma reg 4 tiles",
+    "f16 mfma reg 5 tiles", "f16 mfma reg 6 tiles", "f16 mfma reg 7 tiles", "f16 mfma reg 8 tiles"};
+const char* decode_linear_mfma_variant_name(int id) { return id >= 0 && id < 12 ? DLM_NAMES[id] : nullptr; }
+
+int choose_decode_linear_mfma(int N, int K, int* rows_wg) {
     // Rows per workgroup: the workgroups of a launch should come out as whole rounds over the
     // 256 compute units (a launch of 160 or 448 workgroups leaves units idle for a good part of
     // it: 70B-shape QKV 44 -> 31 us), with as many rows per workgroup as fit (each activation
     // fragment then feeds more row tiles), up to 128.
     constexpr int CUS = 256;
-    const int rounds = ((a.N + CUS - 1) / CUS + 127) / 128;
-    int rows = (a.N + CUS * rounds - 1) / (CUS * rounds);
+    const int rounds = ((N + CUS - 1) / CUS + 127) / 128;
+    int rows = (N + CUS * rounds - 1) / (CUS * rounds);
     rows += rows & 1;   // the pair epilogues need even row offsets
     if (rows < 16) rows = 16;
-    const dim3 grid((a.N + rows - 1) / rows);
+    *rows_wg = rows;
+    const int tiles = (rows + 15) / 16;
     // Weights through an LDS ring of direct loads - unless the row pitch is a power of two: then
     // the rows of a workgroup sit in the same few memory channels, and a workgroup that moves in
     // lockstep from barrier to barrier asks them all at once (70B QKV, K = 8192: 31 -> 44 us, while
     // K = 28672, 13824, 11008 and 5120 gain 9..20 %); the register kernel's waves drift apart.
-    if (rows <= 64 && a.K % 256 == 0 && a.K / 256 >= 8 && (a.K & (a.K - 1)) != 0) {
-        switch ((rows + 15) / 16) {
-            case 1: launch_dl_dma<1, 8>(a, sb, grid, rows, st); break;
-            case 2: launch_dl_dma<2, 6>(a, sb, grid, rows, st); break;
-            case 3: launch_dl_dma<3, 4>(a, sb, grid, rows, st); break;
-            default: launch_dl_dma<4, 3>(a, sb, grid, rows, st); break;
-        }
-        return;
-    }
-    switch ((rows + 15) / 16) {   // one K block in flight per wave; 8 waves split K, 16 for tall workgroups
-        case 1: launch((decode_linear_mfma_kernel<1, 1, 8>), grid, dim3(512), 0, st, a, sb, rows); break;
-        case 2: launch((decode_linear_mfma_kernel<2, 1, 8>), grid, dim3(512), 0, st, a, sb, rows); break;
-        case 3: launch((decode_linear_mfma_kernel<3, 1, 8>), grid, dim3(512), 0, st, a, sb, rows); break;
-        case 4: launch((decode_linear_mfma_kernel<4, 1, 8>), grid, dim3(512), 0, st, a, sb, rows); break;
-        case 5: launch((decode_linear_mfma_kernel<5, 1, 16>), grid, dim3(1024), 0, st, a, sb, rows); break;
-        case 6: launch((decode_linear_mfma_kernel<6, 1, 16>), grid, dim3(1024), 0, st, a, sb, rows); break;
-        case 7: launch((decode_linear_mfma_kernel<7, 1, 16>), grid, dim3(1024), 0, st, a, sb, rows); break;
+    if (rows <= 64 && K % 256 == 0 && K / 256 >= 8 && (K & (K - 1)) != 0) return tiles - 1;
+    return 4 + tiles - 1;
+}
+
+void launch_decode_linear_mfma(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
+    int rows = 0;
+    const int id = choose_decode_linear_mfma(a.N, a.K, &rows);
+    const dim3 grid((a.N + rows - 1) / rows);
+    switch (id) {
+        case 0: launch_dl_dma<1, 8>(a, sb, grid, rows, st); break;
+        case 1: launch_dl_dma<2, 6>(a, sb, grid, rows, st); break;
+        case 2: launch_dl_dma<3, 4>(a, sb, grid, rows, st); break;
+        case 3: launch_dl_dma<4, 3>(a, sb, grid, rows, st); break;
+        // one K block in flight per wave; 8 waves split K, 16 for tall workgroups
+        case 4: launch((decode_linear_mfma_kernel<1, 1, 8>), grid, dim3(512), 0, st, a, sb, rows); break;
+        case 5: launch((decode_linear_mfma_kernel<2, 1, 8>), grid, dim3(512), 0, st, a, sb, rows); break;
+        case 6: launch((decode_linear_mfma_kernel<3, 1, 8>), grid, dim3(512), 0, st, a, sb, rows); break;
+        case 7: launch((decode_linear_mfma_kernel<4, 1, 8>), grid, dim3(512), 0, st, a, sb, rows); break;
+        case 8: launch((decode_linear_mfma_kernel<5, 1, 16>), grid, dim3(1024), 0, st, a, sb, rows); break;
+        case 9: launch((decode_linear_mfma_kernel<6, 1, 16>), grid, dim3(1024), 0, st, a, sb, rows); break;
+        case 10: launch((decode_linear_mfma_kernel<7, 1, 16>), grid, dim3(1024), 0, st, a, sb, rows); break;
         default: launch((decode_linear_mfma_kernel<8, 1, 16>), grid, dim3(1024), 0, st, a, sb, rows); break;
     }
 }
@@ -1016,19 +1050,34 @@ void launch_scale_columns_f16(void* W, const float* gain, int32_t N, int32_t K, 
            static_cast<f16_t*>(W), gain, n8, K, overflow);
 }
 
-__global__ __launch_bounds__(256) void to_half_kernel(const float* __restrict__ x, f16_t* __restrict__ out, size_t n4) {
+__global__ __launch_bounds__(256) void to_half_kernel(const float* __restrict__ x, f16_t* __restrict__ out, size_t n4,
+                                                      uint32_t* oflow) {
     const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
     if (i >= n4) return;
     const float4 t = reinterpret_cast<const float4*>(x)[i];
     typedef _Float16 h4 __attribute__((ext_vector_type(4)));
     h4 o;
-    o[0] = static_cast<f16_t>(t.x); o[1] = static_cast<f16_t>(t.y); o[2] = static_cast<f16_t>(t.z); o[3] = static_cast<f16_t>(t.w);
+    o[0] = store_cast<f16_t>(t.x, oflow); o[1] = store_cast<f16_t>(t.y, oflow);
+    o[2] = store_cast<f16_t>(t.z, oflow); o[3] = store_cast<f16_t>(t.w, oflow);
     reinterpret_cast<h4*>(out)[i] = o;
 }
 
-void launch_to_half(const float* x, void* out, size_t n, hipStream_t st) {
+void launch_to_half(const float* x, void* out, size_t n, uint32_t* oflow, hipStream_t st) {
     const size_t n4 = n / 4;
-    launch(to_half_kernel, dim3(static_cast<unsigned>((n4 + 255) / 256)), dim3(256), 0, st, x, static_cast<f16_t*>(out), n4);
+    launch(to_half_kernel, dim3(static_cast<unsigned>((n4 + 255) / 256)), dim3(256), 0, st, x, static_cast<f16_t*>(out), n4, oflow);
+}
+
+// One-time kernel attribute calls happen inside the launchers; their first failure is kept here.
+static std::atomic<int> g_attr_error{static_cast<int>(hipSuccess)};
+static std::atomic<bool> g_attr_injected{false};
+hipError_t kernel_attribute_error() {
+    if (g_attr_injected.load()) return hipErrorInvalidValue;
+    return static_cast<hipError_t>(g_attr_error.load());
+}
+void inject_kernel_attribute_error(bool on) { g_attr_injected.store(on); }
+void note_kernel_attribute(hipError_t e) {
+    int none = static_cast<int>(hipSuccess);
+    if (e != hipSuccess) g_attr_error.compare_exchange_strong(none, static_cast<int>(e));
 }
 
 // bf16 -> half, in place, 8 elements per thread

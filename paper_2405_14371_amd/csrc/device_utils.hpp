@@ -23,6 +23,20 @@ template <> struct Elem<f16_t> {
     __device__ static __forceinline__ f16_t from_f32(float v) { return static_cast<f16_t>(v); }
 };
 
+// Rounding an activation or cache value to its stored type.  IEEE half ends at 65504: a value
+// beyond it (or a NaN) sets *oflow, a word in host-visible memory that the runtime tests
+// before every call (plain store of the same value from every lane that sees one: no atomic
+// needed, and no traffic at all in the normal case).  fp32 stores pass through.
+template <typename T>
+__device__ __forceinline__ T store_cast(float v, uint32_t* oflow);
+template <>
+__device__ __forceinline__ float store_cast<float>(float v, uint32_t*) { return v; }
+template <>
+__device__ __forceinline__ f16_t store_cast<f16_t>(float v, uint32_t* oflow) {
+    if (!(fabsf(v) <= 65504.0f)) *oflow = 1u;
+    return static_cast<f16_t>(v);
+}
+
 // Activation / KV-cache element type that goes with a weight element type.
 template <typename WT> struct ActOf;
 template <> struct ActOf<float> { typedef float type; };

@@ -95,6 +95,7 @@ struct DecodeLinear {
     int32_t norm_xb;       // non-zero: xb is un-normalised; scale row b of the result by
                            // rsqrt(mean_k xb[b][k]^2 + eps) (RMSNorm with the gain folded into W)
     void* out_h;           // EPI_RESID: non-null -> also store the result as half [nb, N]
+    uint32_t* oflow;       // set to 1 when a value stored as half leaves half's range (16-bit weights only)
 };
 void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st);
 // same contract with xb/out_b; requires wt == DT_F16, nb <= 16, K % 64 == 0, gain == null
@@ -145,8 +146,19 @@ struct PrefillGemm {
     float* part;
     size_t part_cap;
     int32_t kslices;
+    uint32_t* oflow;       // set to 1 when a value stored as half leaves half's range (half operands only)
 };
 void launch_prefill_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st);
+
+// Which kernel variant a launch takes - pure host functions of the shape, the same ones the
+// launchers call.  Each returns an index into its family's name table (name(id) is null past
+// the end of the table).
+int choose_prefill_gemm(int dt, int M, int N, int K, int epi, bool has_part, size_t part_cap, int* kslices);
+const char* prefill_gemm_variant_name(int id);
+int choose_decode_linear(int wt, int nb, int N, int K);
+const char* decode_linear_variant_name(int id);
+int choose_decode_linear_mfma(int N, int K, int* rows_wg);
+const char* decode_linear_mfma_variant_name(int id);
 
 struct PrefillAttn {
     const float* q;        // [B*T, hq*dh] fp32, rotated
@@ -161,8 +173,15 @@ void launch_prefill_attn(const PrefillAttn& a, const SeqBatch& sb, hipStream_t s
 // W[n][k] *= gain[k] for a half matrix [N, K] (RMSNorm gains folded into the matrix that
 // consumes the normalised vector); *overflow is set when a product leaves half's range.
 void launch_scale_columns_f16(void* W, const float* gain, int32_t N, int32_t K, uint32_t* overflow, hipStream_t st);
-// out[i] = half(x[i]), i < n (n a multiple of 4)
-void launch_to_half(const float* x, void* out, size_t n, hipStream_t st);
+// out[i] = half(x[i]), i < n (n a multiple of 4); *oflow is set when a value leaves half's range
+void launch_to_half(const float* x, void* out, size_t n, uint32_t* oflow, hipStream_t st);
+
+// First failure of a one-time kernel attribute call (the opt-in to more than 64 KB of LDS per
+// workgroup), hipSuccess if none: the runtime reports it instead of a later launch error.
+hipError_t kernel_attribute_error();
+void note_kernel_attribute(hipError_t e);
+// test hook: pretend such a call failed (true) / forget the pretended failure (false)
+void inject_kernel_attribute_error(bool on);
 
 // In place: n bf16 values -> n IEEE half values (round to nearest; exact for every bf16 in
 // half's normal range).  *overflow is set when a finite value exceeds half's range.

@@ -39,7 +39,7 @@ bool valid(const shard_plan_problem* p) {
 
 }  // namespace
 
-extern "C" int shard_plan_latency(const shard_plan_problem* p, int32_t* device_of_layer, double* t_total) {
+static int plan_latency_impl(const shard_plan_problem* p, int32_t* device_of_layer, double* t_total) {
     if (!valid(p) || !device_of_layer || !t_total) return -1;
     const View v{p, p->n_layers, p->n_devices};
     const int N = v.N, M = v.M;
@@ -83,8 +83,8 @@ extern "C" int shard_plan_latency(const shard_plan_problem* p, int32_t* device_o
     return 0;
 }
 
-extern "C" int shard_plan_throughput(const shard_plan_problem* p, int32_t with_return_hop, int32_t* device_of_layer,
-                                     double* t_slowest_stage) {
+static int plan_throughput_impl(const shard_plan_problem* p, int32_t with_return_hop, int32_t* device_of_layer,
+                                double* t_slowest_stage) {
     if (!valid(p) || !device_of_layer || !t_slowest_stage || p->n_devices > 16) return -1;
     const View v{p, p->n_layers, p->n_devices};
     const int N = v.N, M = v.M;
@@ -168,5 +168,65 @@ extern "C" int shard_plan_throughput(const shard_plan_problem* p, int32_t with_r
         c = b.c;
     }
     *t_slowest_stage = best;
+    return 0;
+}
+
+// Nothing throws across the C boundary: a failed host allocation or thread start is -3.
+extern "C" int shard_plan_latency(const shard_plan_problem* p, int32_t* device_of_layer, double* t_total) {
+    try {
+        return plan_latency_impl(p, device_of_layer, t_total);
+    } catch (...) {
+        return -3;
+    }
+}
+
+extern "C" int shard_plan_throughput(const shard_plan_problem* p, int32_t with_return_hop, int32_t* device_of_layer,
+                                     double* t_slowest_stage) {
+    try {
+        return plan_throughput_impl(p, with_return_hop, device_of_layer, t_slowest_stage);
+    } catch (...) {
+        return -3;
+    }
+}
+
+extern "C" int shard_plan_to_stages(int32_t n_layers, int32_t n_devices, const int32_t* device_of_layer,
+                                    const double* t_prefill, const double* t_decode, const double* act_prefill,
+                                    const double* act_decode, const double* bandwidth, int32_t* n_stages,
+                                    int32_t* stage_device, double* t_stage_prefill, double* t_stage_decode,
+                                    double* c_prefill, double* c_decode, double* c_return) {
+    if (n_layers < 1 || n_devices < 1 || !device_of_layer || !t_prefill || !t_decode || !act_prefill || !act_decode ||
+        !bandwidth || !n_stages || !stage_device || !t_stage_prefill || !t_stage_decode || !c_prefill || !c_decode || !c_return)
+        return -1;
+    const int N = n_layers, M = n_devices;
+    for (int i = 0; i < N; ++i)
+        if (device_of_layer[i] < 0 || device_of_layer[i] >= M) return -1;
+    auto link = [&](int k, int j) { return bandwidth[static_cast<size_t>(k) * M + j]; };
+    int S = 0;
+    for (int i = 0; i < N; ++i) {
+        const int dev = device_of_layer[i];
+        if (i == 0 || dev != device_of_layer[i - 1]) {
+            for (int s = 0; s < S; ++s)
+                if (stage_device[s] == dev) return -2;   // the device already closed a range
+            if (S > 0) {                                 // Eq. 1 for the activation that crosses into the new stage
+                const double bw = link(stage_device[S - 1], dev);
+                if (!(bw > 0.0)) return -1;
+                c_prefill[S - 1] = act_prefill[i - 1] / bw;
+                c_decode[S - 1] = act_decode[i - 1] / bw;
+            }
+            stage_device[S] = dev;
+            t_stage_prefill[S] = 0.0;
+            t_stage_decode[S] = 0.0;
+            ++S;
+        }
+        t_stage_prefill[S - 1] += t_prefill[static_cast<size_t>(i) * M + dev];   // the compute term of Eq. 9
+        t_stage_decode[S - 1] += t_decode[static_cast<size_t>(i) * M + dev];
+    }
+    *c_return = 0.0;
+    if (stage_device[S - 1] != stage_device[0]) {
+        const double bw = link(stage_device[S - 1], stage_device[0]);
+        if (!(bw > 0.0)) return -1;
+        *c_return = act_decode[N - 1] / bw;
+    }
+    *n_stages = S;
     return 0;
 }

@@ -72,8 +72,8 @@ __device__ __forceinline__ void gemm_epilogue(const PrefillGemm& a, const SeqBat
     if (a.epi == EPI_SWIGLU) {
         const int F = a.N / 2;
         ET* op = static_cast<ET*>(a.out_act) + static_cast<size_t>(m) * F + n4 / 2;
-        op[0] = Elem<ET>::from_f32(val[0] / (1.0f + expf(-val[0])) * val[1]);
-        op[1] = Elem<ET>::from_f32(val[2] / (1.0f + expf(-val[2])) * val[3]);
+        op[0] = store_cast<ET>(val[0] / (1.0f + expf(-val[0])) * val[1], a.oflow);
+        op[1] = store_cast<ET>(val[2] / (1.0f + expf(-val[2])) * val[3], a.oflow);
         return;
     }
     // EPI_QKV
@@ -100,7 +100,7 @@ __device__ __forceinline__ void gemm_epilogue(const PrefillGemm& a, const SeqBat
     const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
     ET* dst = static_cast<ET*>(is_k ? a.kv.k : a.kv.v) + at;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) dst[i] = Elem<ET>::from_f32(r[i]);
+    for (int i = 0; i < 4; ++i) dst[i] = store_cast<ET>(r[i], a.oflow);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -272,8 +272,8 @@ static void launch_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st
     constexpr size_t lds = 2u * (BN + BM) * PITCH * sizeof(float);
     static std::once_flag once;  // more than 64 KB of LDS per workgroup is an opt-in
     std::call_once(once, [] {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<T, BN, BM, ROWDW, PITCH>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        note_kernel_attribute(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<T, BN, BM, ROWDW, PITCH>),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
     });
     launch((gemm_kernel<T, BN, BM, ROWDW, PITCH>), dim3(grid), dim3(256), lds, st, a, sb, tiles_m, total);
 }
@@ -418,8 +418,8 @@ static void launch_gemm_dma(const PrefillGemm& a, const SeqBatch& sb, hipStream_
     static_assert(lds <= 160 * 1024, "LDS of a compute unit");
     static std::once_flag once;  // more than 64 KB of LDS per workgroup is an opt-in
     std::call_once(once, [] {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_dma_kernel<T, BN, BM, ROWDW, STAGES, WN, WM>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        note_kernel_attribute(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_dma_kernel<T, BN, BM, ROWDW, STAGES, WN, WM>),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
     });
     launch(gemm_dma_kernel<T, BN, BM, ROWDW, STAGES, WN, WM>, dim3(grid, a.kslices > 1 ? a.kslices : 1), dim3(64 * WN * WM), lds,
            st, a, sb, tiles_m, total);
@@ -467,46 +467,48 @@ static int pick_variant(const GemmVariant* v, int count, int M, int N) {
     return best;
 }
 
-static void launch_gemm_f32(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
-    if (a.K % 16 == 0) {  // direct-to-LDS variants (k-step of 16 or 32)
-        static const GemmVariant v[] = {{128, 128, 2, {100.f, 142.f, 0.f}},
-                                        {128, 64, 3, {125.f, 120.f, 116.f}},
-                                        {192, 64, 2, {118.f, 138.f, 0.f}},   // 12288 x 512: two tiles per unit, both resident
-                                        {192, 128, 2, {136.f, 144.f, 0.f}},  // 22016 x 512: 460 tiles, at most two per unit
-                                        {128, 64, 2, {116.f, 131.f, 0.f}}};  // k-step 32
-        // at most one 128 x 64 tile per compute unit (projections back to d_model at M = 512): two
-        // K slices put two workgroups on every unit (alone: O 145 -> 136 us, down 364 -> 343 us
-        // with the reduction; three slices lose)
-        if (a.epi == EPI_RESID && a.part) {
-            const long t64 = static_cast<long>((a.M + 63) / 64) * ((a.N + 127) / 128);
-            const size_t elems = static_cast<size_t>(a.M) * a.N;
-            if (t64 > 128 && t64 <= 256 && a.K >= 2048 && elems % 4 == 0 && elems * 2 <= a.part_cap) {
-                PrefillGemm as = a;
-                as.kslices = 2;
-                launch_gemm_dma<float, 128, 64, 16, 4, 2, 2>(as, sb, st);
-                launch(splitk_reduce_kernel, dim3(static_cast<unsigned>((elems / 4 + 255) / 256)), dim3(256), 0, st,
-                       static_cast<const float*>(a.part), 2, elems, a.resid, a.out);
-                return;
-            }
-        }
-        switch (pick_variant(v, a.K % 32 == 0 ? 5 : 4, a.M, a.N)) {
-            case 0: launch_gemm_dma<float, 128, 128, 16, 4, 2, 2>(a, sb, st); break;
-            case 1: launch_gemm_dma<float, 128, 64, 16, 4, 2, 2>(a, sb, st); break;
-            case 2: launch_gemm_dma<float, 192, 64, 16, 4, 2, 2>(a, sb, st); break;
-            case 3: launch_gemm_dma<float, 192, 128, 16, 4, 2, 2>(a, sb, st); break;
-            default: launch_gemm_dma<float, 128, 64, 32, 3, 2, 2>(a, sb, st); break;
-        }
-        return;
-    }
-    static const GemmVariant v[] = {{128, 128, 3, {108.f, 128.f, 133.f}}, {128, 64, 3, {101.f, 119.f, 125.f}}};
-    switch (pick_variant(v, 2, a.M, a.N)) {
-        case 0: launch_gemm<float, 128, 128, 16, 16>(a, sb, st); break;
-        default: launch_gemm<float, 128, 64, 32, 32>(a, sb, st); break;
-    }
-}
+// Every variant the launchers below can take, by name: the selection (choose_prefill_gemm) is
+// a pure host function of the shape, so that tests can ask which variant a shape lands on.
+enum GemmId {
+    G32_DMA_128x128, G32_DMA_128x64, G32_DMA_192x64, G32_DMA_192x128, G32_DMA_128x64_K32, G32_DMA_128x64_SPLITK2,
+    G32_REG_128x128, G32_REG_128x64,
+    G16_DMA_256x256, G16_DMA_256x128, G16_DMA_128x128, G16_DMA_128x64, G16_DMA_384x128, G16_DMA_64x64,
+    G16_DMA_128x64_SPLITK, G16_REG_128x128_K32, G16_REG_128x128_K64, G16_REG_128x64,
+    GEMM_ID_COUNT
+};
+static const char* const GEMM_NAMES[GEMM_ID_COUNT] = {
+    "f32 dma 128x128", "f32 dma 128x64", "f32 dma 192x64", "f32 dma 192x128", "f32 dma 128x64 k32", "f32 dma 128x64 split-k 2",
+    "f32 reg 128x128", "f32 reg 128x64",
+    "f16 dma 256x256", "f16 dma 256x128", "f16 dma 128x128", "f16 dma 128x64", "f16 dma 384x128", "f16 dma 64x64",
+    "f16 dma 128x64 split-k", "f16 reg 128x128 k32", "f16 reg 128x128 k64", "f16 reg 128x64",
+};
+const char* prefill_gemm_variant_name(int id) { return id >= 0 && id < GEMM_ID_COUNT ? GEMM_NAMES[id] : nullptr; }
 
-static void launch_gemm_f16(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
-    if (a.K % 64 == 0) {  // direct-to-LDS variants (k-step of 64)
+int choose_prefill_gemm(int dt, int M, int N, int K, int epi, bool has_part, size_t part_cap, int* kslices) {
+    *kslices = 1;
+    const size_t elems = static_cast<size_t>(M) * N;
+    const long t64 = static_cast<long>((M + 63) / 64) * ((N + 127) / 128);
+    if (dt == DT_F32) {
+        if (K % 16 == 0) {  // direct-to-LDS variants (k-step of 16 or 32)
+            static const GemmVariant v[] = {{128, 128, 2, {100.f, 142.f, 0.f}},
+                                            {128, 64, 3, {125.f, 120.f, 116.f}},
+                                            {192, 64, 2, {118.f, 138.f, 0.f}},   // 12288 x 512: two tiles per unit, both resident
+                                            {192, 128, 2, {136.f, 144.f, 0.f}},  // 22016 x 512: 460 tiles, at most two per unit
+                                            {128, 64, 2, {116.f, 131.f, 0.f}}};  // k-step 32
+            // at most one 128 x 64 tile per compute unit (projections back to d_model at M = 512): two
+            // K slices put two workgroups on every unit (alone: O 145 -> 136 us, down 364 -> 343 us
+            // with the reduction; three slices lose)
+            if (epi == EPI_RESID && has_part && t64 > 128 && t64 <= 256 && K >= 2048 && elems % 4 == 0 && elems * 2 <= part_cap) {
+                *kslices = 2;
+                return G32_DMA_128x64_SPLITK2;
+            }
+            static const int ids[] = {G32_DMA_128x128, G32_DMA_128x64, G32_DMA_192x64, G32_DMA_192x128, G32_DMA_128x64_K32};
+            return ids[pick_variant(v, K % 32 == 0 ? 5 : 4, M, N)];
+        }
+        static const GemmVariant v[] = {{128, 128, 3, {108.f, 128.f, 133.f}}, {128, 64, 3, {101.f, 119.f, 125.f}}};
+        return pick_variant(v, 2, M, N) == 0 ? G32_REG_128x128 : G32_REG_128x64;
+    }
+    if (K % 64 == 0) {  // direct-to-LDS variants (k-step of 64)
         static const GemmVariant v[] = {{256, 256, 1, {1500.f, 0.f, 0.f}},
                                         {256, 128, 1, {1250.f, 0.f, 0.f}},
                                         {128, 128, 1, {1000.f, 0.f, 0.f}},
@@ -517,44 +519,55 @@ static void launch_gemm_f16(const PrefillGemm& a, const SeqBatch& sb, hipStream_
         // the smallest tile (13B shape, M = 256: 160 tiles): K is split over 3 or 4 workgroup rows,
         // about two workgroups per compute unit in all, each at least 8 k-steps (measured alone:
         // O 40 -> 35 us, down 102 -> 76 us; two slices gain nothing over the unsplit launch).
-        if (a.epi == EPI_RESID && a.part) {
-            const long t64 = static_cast<long>((a.M + 63) / 64) * ((a.N + 127) / 128);
+        if (epi == EPI_RESID && has_part) {
             long S = 512 / t64;
             if (S > 4) S = 4;
-            if (S > a.K / 64 / 8) S = a.K / 64 / 8;
-            const size_t elems = static_cast<size_t>(a.M) * a.N;
-            if (S >= 3 && elems % 4 == 0 && elems * S <= a.part_cap) {
-                PrefillGemm as = a;
-                as.kslices = static_cast<int32_t>(S);
-                launch_gemm_dma<f16_t, 128, 64, 32, 3, 2, 2>(as, sb, st);
-                launch(splitk_reduce_kernel, dim3(static_cast<unsigned>((elems / 4 + 255) / 256)), dim3(256), 0, st,
-                       static_cast<const float*>(a.part), as.kslices, elems, a.resid, a.out);
-                return;
+            if (S > K / 64 / 8) S = K / 64 / 8;
+            if (S >= 3 && elems % 4 == 0 && elems * S <= part_cap) {
+                *kslices = static_cast<int>(S);
+                return G16_DMA_128x64_SPLITK;
             }
         }
-        switch (pick_variant(v, 6, a.M, a.N)) {
-            case 5: launch_gemm_dma<f16_t, 64, 64, 32, 6, 2, 2>(a, sb, st); break;
-            case 0: launch_gemm_dma<f16_t, 256, 256, 32, 2, 4, 2>(a, sb, st); break;
-            case 1: launch_gemm_dma<f16_t, 256, 128, 32, 3, 4, 2>(a, sb, st); break;
-            case 2: launch_gemm_dma<f16_t, 128, 128, 32, 3, 2, 2>(a, sb, st); break;
-            case 3: launch_gemm_dma<f16_t, 128, 64, 32, 3, 2, 2>(a, sb, st); break;
-            default: launch_gemm_dma<f16_t, 384, 128, 32, 2, 4, 2>(a, sb, st); break;
-        }
-        return;
+        static const int ids[] = {G16_DMA_256x256, G16_DMA_256x128, G16_DMA_128x128, G16_DMA_128x64, G16_DMA_384x128, G16_DMA_64x64};
+        return ids[pick_variant(v, 6, M, N)];
     }
     static const GemmVariant v[] = {{128, 128, 3, {390.f, 650.f, 850.f}},
                                     {128, 128, 2, {470.f, 800.f, 0.f}},
                                     {128, 64, 3, {270.f, 490.f, 700.f}}};
-    switch (pick_variant(v, 3, a.M, a.N)) {
-        case 0: launch_gemm<f16_t, 128, 128, 16, 16>(a, sb, st); break;
-        case 1: launch_gemm<f16_t, 128, 128, 32, 32>(a, sb, st); break;
-        default: launch_gemm<f16_t, 128, 64, 32, 32>(a, sb, st); break;
-    }
+    static const int ids[] = {G16_REG_128x128_K32, G16_REG_128x128_K64, G16_REG_128x64};
+    return ids[pick_variant(v, 3, M, N)];
 }
 
 void launch_prefill_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t st) {
-    if (a.dt == DT_F32) launch_gemm_f32(a, sb, st);
-    else launch_gemm_f16(a, sb, st);
+    int kslices = 1;
+    const int id = choose_prefill_gemm(a.dt, a.M, a.N, a.K, a.epi, a.part != nullptr, a.part_cap, &kslices);
+    PrefillGemm as = a;
+    as.kslices = kslices;
+    switch (id) {
+        case G32_DMA_128x128: launch_gemm_dma<float, 128, 128, 16, 4, 2, 2>(as, sb, st); break;
+        case G32_DMA_128x64: launch_gemm_dma<float, 128, 64, 16, 4, 2, 2>(as, sb, st); break;
+        case G32_DMA_192x64: launch_gemm_dma<float, 192, 64, 16, 4, 2, 2>(as, sb, st); break;
+        case G32_DMA_192x128: launch_gemm_dma<float, 192, 128, 16, 4, 2, 2>(as, sb, st); break;
+        case G32_DMA_128x64_K32: launch_gemm_dma<float, 128, 64, 32, 3, 2, 2>(as, sb, st); break;
+        case G32_DMA_128x64_SPLITK2: launch_gemm_dma<float, 128, 64, 16, 4, 2, 2>(as, sb, st); break;
+        case G32_REG_128x128: launch_gemm<float, 128, 128, 16, 16>(as, sb, st); break;
+        case G32_REG_128x64: launch_gemm<float, 128, 64, 32, 32>(as, sb, st); break;
+        case G16_DMA_256x256: launch_gemm_dma<f16_t, 256, 256, 32, 2, 4, 2>(as, sb, st); break;
+        case G16_DMA_256x128: launch_gemm_dma<f16_t, 256, 128, 32, 3, 4, 2>(as, sb, st); break;
+        case G16_DMA_128x128: launch_gemm_dma<f16_t, 128, 128, 32, 3, 2, 2>(as, sb, st); break;
+        case G16_DMA_128x64: launch_gemm_dma<f16_t, 128, 64, 32, 3, 2, 2>(as, sb, st); break;
+        case G16_DMA_384x128: launch_gemm_dma<f16_t, 384, 128, 32, 2, 4, 2>(as, sb, st); break;
+        case G16_DMA_64x64: launch_gemm_dma<f16_t, 64, 64, 32, 6, 2, 2>(as, sb, st); break;
+        case G16_DMA_128x64_SPLITK: launch_gemm_dma<f16_t, 128, 64, 32, 3, 2, 2>(as, sb, st); break;
+        case G16_REG_128x128_K32: launch_gemm<f16_t, 128, 128, 16, 16>(as, sb, st); break;
+        case G16_REG_128x128_K64: launch_gemm<f16_t, 128, 128, 32, 32>(as, sb, st); break;
+        default: launch_gemm<f16_t, 128, 64, 32, 32>(as, sb, st); break;
+    }
+    if (kslices > 1) {
+        const size_t elems = static_cast<size_t>(a.M) * a.N;
+        launch(splitk_reduce_kernel, dim3(static_cast<unsigned>((elems / 4 + 255) / 256)), dim3(256), 0, st,
+               static_cast<const float*>(a.part), kslices, elems, a.resid, a.out);
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1085,8 +1098,8 @@ static void launch_pa_lds_q(const PrefillAttn& a, const SeqBatch& sb, hipStream_
                   "the merge buffer lives in the ring");
     static std::once_flag once;  // more than 64 KB of LDS per workgroup is an opt-in
     std::call_once(once, [] {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_attn_lds_kernel<KT, DH, KS, STAGES, QT>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        note_kernel_attribute(hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_attn_lds_kernel<KT, DH, KS, STAGES, QT>),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
     });
     const dim3 grid((a.T + 32 * QT - 1) / (32 * QT), a.hq, a.B);
     launch(prefill_attn_lds_kernel<KT, DH, KS, STAGES, QT>, grid, dim3(64 * QT * KS), lds, st, a, sb);

@@ -25,8 +25,7 @@ bool good(double v) { return std::isfinite(v) && v >= 0.0; }
 
 }  // namespace
 
-extern "C" int shard_simulate_pipeline(const shard_pipeline_problem* p, int32_t no_bubbles, double* makespan_s,
-                                       double* busy_s) {
+static int simulate_impl(const shard_pipeline_problem* p, int32_t no_bubbles, double* makespan_s, double* busy_s) {
     if (!p || !makespan_s || p->n_stages < 1 || p->n_micro < 1 || p->n_decode < 0 || !p->t_prefill || !p->t_decode)
         return -1;
     const int S = p->n_stages, MB = p->n_micro, IT = 1 + p->n_decode;
@@ -85,4 +84,14 @@ extern "C" int shard_simulate_pipeline(const shard_pipeline_problem* p, int32_t 
     if (busy_s)
         for (int s = 0; s < S; ++s) busy_s[s] = busy[s];
     return 0;
+}
+
+// Nothing throws across the C boundary: a failed host allocation is -3.
+extern "C" int shard_simulate_pipeline(const shard_pipeline_problem* p, int32_t no_bubbles, double* makespan_s,
+                                       double* busy_s) {
+    try {
+        return simulate_impl(p, no_bubbles, makespan_s, busy_s);
+    } catch (...) {
+        return -3;
+    }
 }

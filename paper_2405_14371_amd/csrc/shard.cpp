@@ -3,6 +3,7 @@
 // autoregressive phase.  All arithmetic of the layer happens in the kernels; this file
 // only moves pointers.
 #include "../../include/shard.h"
+#include "../../include/shard_introspect.h"
 
 #include <hip/hip_runtime.h>
 
@@ -10,6 +11,8 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <exception>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -104,6 +107,7 @@ struct shard {
     int nsplit_max = 32;
     Timing timing;
     uint32_t* cvt_flag = nullptr;   // overflow flag of the bf16 -> half conversion during create
+    uint32_t* oflow = nullptr;      // host-visible (pinned, mapped) word: a half store left half's range
     std::vector<hipEvent_t> layer_ev;  // L+1 events, used by shard_profile
     bool record_layers = false;
 };
@@ -119,6 +123,7 @@ void free_all(shard* s) {
     void* ptrs[] = {s->rope, s->block_table, s->cvt_flag};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
+    if (s->oflow) (void)hipHostFree(s->oflow);
     for (auto& w : s->work) {
         void* wp[] = {w.h, w.q, w.o, w.f, w.part_o, w.part_ml, w.splitk};
         for (void* p : wp)
@@ -149,6 +154,11 @@ int validate_cfg(const shard_model_cfg* m, const shard_kv_cfg* kv, int lo, int h
         return fail(SHARD_E_INVAL, "bad KV configuration");
     if (static_cast<uint64_t>(kv->max_seq_len) * static_cast<uint64_t>(kv->page_size) >= (1ull << 32))
         return fail(SHARD_E_INVAL, "max_seq_len * page_size must be below 2^32");
+    const uint64_t pages = (static_cast<uint64_t>(kv->max_seq_len) + kv->page_size - 1) / kv->page_size * static_cast<uint64_t>(kv->max_seqs);
+    if (pages >= (1ull << 31)) return fail(SHARD_E_INVAL, "max_seqs * ceil(max_seq_len / page_size) must be below 2^31 pages");
+    if (static_cast<uint64_t>(m->n_heads) * m->head_dim >= (1ull << 24) || static_cast<uint64_t>(m->d_model) >= (1ull << 24) ||
+        static_cast<uint64_t>(m->ffn_dim) >= (1ull << 24))
+        return fail(SHARD_E_INVAL, "model widths must be below 2^24");
     return SHARD_OK;
 }
 
@@ -262,7 +272,7 @@ void run_prefill(shard* s, shard::Work& wk, const SeqBatch& sb, int T, const flo
             launch_rmsnorm(x, l.g_attn, m.rms_eps, wk.h, adt, M, m.d_model, st);
         }
         PrefillGemm g{};
-        g.M = M; g.dt = dt; g.T = T; g.hq = m.n_heads; g.kv = kv_view(s, li); g.rope = s->rope;
+        g.M = M; g.dt = dt; g.T = T; g.hq = m.n_heads; g.kv = kv_view(s, li); g.rope = s->rope; g.oflow = s->oflow;
         g.A = wk.h; g.W = l.wqkv; g.N = s->nqkv; g.K = m.d_model; g.epi = EPI_QKV; g.q = wk.q;
         {
             Bracket t(s, SHARD_K_PREFILL_QKV, st);
@@ -318,6 +328,14 @@ int pick_nsplit(const shard* s, const SeqBatch& sb) {
     return n < 1 ? 1 : n;
 }
 
+// Whether a decode step of B sequences takes the matrix-core projections (run_decode_mfma):
+// 16-bit weights, more than 4 sequences, and every inner dimension a multiple of the MFMA
+// kernels' 64-element K block; otherwise the streaming kernels carry up to 8 rows per pass.
+bool decode_on_matrix_cores(const shard_model_cfg& m, int B) {
+    return m.weight_dtype != SHARD_F32 && B > 4 && m.d_model % 64 == 0 && m.ffn_dim % 64 == 0 &&
+           (m.n_heads * m.head_dim) % 64 == 0;
+}
+
 // Decode step with 16-bit weights and more than 4 sequences: projections on the matrix
 // cores, one pass over the weights per group of up to 16 sequences (the streaming kernels'
 // vector ALUs fall behind the HBM stream from about 8 rows on).  No RMSNorm launches: the
@@ -330,7 +348,7 @@ void run_decode_mfma(shard* s, shard::Work& wk, const SeqBatch& all, const float
     mark_layer(s, 0, st);
     {
         Bracket t(s, SHARD_K_DECODE_QKV, st);
-        launch_to_half(x_in, wk.h, static_cast<size_t>(all.n) * d_model, st);
+        launch_to_half(x_in, wk.h, static_cast<size_t>(all.n) * d_model, s->oflow, st);
     }
     for (int li = 0; li < s->L; ++li) {
         const LayerDev& l = s->layers[li];
@@ -344,7 +362,7 @@ void run_decode_mfma(shard* s, shard::Work& wk, const SeqBatch& all, const float
             float* y = x_out + static_cast<size_t>(b0) * d_model;
             void* xh = static_cast<char*>(wk.h) + static_cast<size_t>(b0) * d_model * 2;   // half copy of the residual stream
             DecodeLinear d{};
-            d.wt = DT_F16; d.nb = B; d.hq = m.n_heads; d.kv = kvv; d.rope = s->rope; d.eps = m.rms_eps;
+            d.wt = DT_F16; d.nb = B; d.hq = m.n_heads; d.kv = kvv; d.rope = s->rope; d.eps = m.rms_eps; d.oflow = s->oflow;
             {
                 Bracket t(s, SHARD_K_DECODE_QKV, st);
                 d.W = l.wqkv; d.N = s->nqkv; d.K = d_model; d.xb = xh; d.norm_xb = 1; d.epi = EPI_QKV; d.q = wk.q;
@@ -384,7 +402,7 @@ void run_decode(shard* s, shard::Work& wk, const SeqBatch& sb, const float* x_in
     const shard_model_cfg& m = s->m;
     const int dt = m.weight_dtype == SHARD_F32 ? DT_F32 : DT_F16;
     const int B = sb.n;
-    if (dt == DT_F16 && B > 4 && m.d_model % 64 == 0 && m.ffn_dim % 64 == 0 && s->nq % 64 == 0) {
+    if (decode_on_matrix_cores(m, B)) {
         run_decode_mfma(s, wk, sb, x_in, x_out, st);
         return;
     }
@@ -405,6 +423,7 @@ void run_decode(shard* s, shard::Work& wk, const SeqBatch& sb, const float* x_in
             d.W = l.wqkv; d.N = s->nqkv; d.K = m.d_model; d.wt = dt; d.nb = nb;
             d.x = x + static_cast<size_t>(b0) * m.d_model; d.gain = l.g_attn; d.eps = m.rms_eps;
             d.epi = EPI_QKV; d.q = wk.q + static_cast<size_t>(b0) * s->nq; d.hq = m.n_heads; d.kv = kvv; d.rope = s->rope;
+            d.oflow = s->oflow;
             Bracket t(s, SHARD_K_DECODE_QKV, st);
             launch_decode_linear(d, sub, st);
         }
@@ -420,7 +439,7 @@ void run_decode(shard* s, shard::Work& wk, const SeqBatch& sb, const float* x_in
             const int nb = B - b0 < 8 ? B - b0 : 8;
             DecodeLinear d{};
             d.W = l.wo; d.N = m.d_model; d.K = s->nq; d.wt = dt; d.nb = nb;
-            d.x = o + static_cast<size_t>(b0) * s->nq; d.epi = EPI_RESID;
+            d.x = o + static_cast<size_t>(b0) * s->nq; d.epi = EPI_RESID; d.oflow = s->oflow;
             d.resid = x + static_cast<size_t>(b0) * m.d_model; d.out = x_out + static_cast<size_t>(b0) * m.d_model;
             Bracket t(s, SHARD_K_DECODE_O, st);
             launch_decode_linear(d, sb, st);
@@ -430,7 +449,7 @@ void run_decode(shard* s, shard::Work& wk, const SeqBatch& sb, const float* x_in
             DecodeLinear d{};
             d.W = l.wgu; d.N = 2 * m.ffn_dim; d.K = m.d_model; d.wt = dt; d.nb = nb;
             d.x = x_out + static_cast<size_t>(b0) * m.d_model; d.gain = l.g_ffn; d.eps = m.rms_eps;
-            d.epi = EPI_SWIGLU; d.out = f + static_cast<size_t>(b0) * m.ffn_dim;
+            d.epi = EPI_SWIGLU; d.out = f + static_cast<size_t>(b0) * m.ffn_dim; d.oflow = s->oflow;
             Bracket t(s, SHARD_K_DECODE_GATEUP, st);
             launch_decode_linear(d, sb, st);
         }
@@ -438,7 +457,7 @@ void run_decode(shard* s, shard::Work& wk, const SeqBatch& sb, const float* x_in
             const int nb = B - b0 < 8 ? B - b0 : 8;
             DecodeLinear d{};
             d.W = l.wd; d.N = m.d_model; d.K = m.ffn_dim; d.wt = dt; d.nb = nb;
-            d.x = f + static_cast<size_t>(b0) * m.ffn_dim; d.epi = EPI_RESID;
+            d.x = f + static_cast<size_t>(b0) * m.ffn_dim; d.epi = EPI_RESID; d.oflow = s->oflow;
             d.resid = x_out + static_cast<size_t>(b0) * m.d_model; d.out = x_out + static_cast<size_t>(b0) * m.d_model;
             Bracket t(s, SHARD_K_DECODE_DOWN, st);
             launch_decode_linear(d, sb, st);
@@ -478,7 +497,82 @@ int release_work(shard::Work* w, hipStream_t st) {
 int check_launch() {
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(SHARD_E_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+    const hipError_t a = shk::kernel_attribute_error();
+    if (a != hipSuccess)
+        return fail(SHARD_E_HIP, "opting a kernel into more than 64 KB of LDS failed: %s", hipGetErrorString(a));
     return SHARD_OK;
+}
+
+// Undo of grow_sequences for a call that failed after it: the pages go back on the stack in
+// the order they came off (the block-table entries a failed call wrote are beyond seq_pages
+// and therefore unused).
+struct GrowUndo {
+    shard* s;
+    int n;
+    int32_t seq[SHARD_MAX_BATCH], pages[SHARD_MAX_BATCH];
+    GrowUndo(shard* sh, const SeqBatch& sb) : s(sh), n(sb.n) {
+        for (int b = 0; b < n; ++b) { seq[b] = sb.seq[b]; pages[b] = sh->seq_pages[sb.seq[b]]; }
+    }
+    void rollback() {
+        for (int b = n - 1; b >= 0; --b)
+            while (s->seq_pages[seq[b]] > pages[b]) {
+                const int idx = seq[b] * s->max_pages + --s->seq_pages[seq[b]];
+                s->free_pages.push_back(s->host_table[idx]);
+            }
+    }
+};
+
+int range_check(const shard* s) {
+    if (s->oflow && *static_cast<volatile uint32_t*>(s->oflow))
+        return fail(SHARD_E_RANGE, "an activation or KV-cache value left the range of IEEE half (65504) in an earlier call; "
+                                   "see shard_overflow");
+    return SHARD_OK;
+}
+
+}  // namespace
+
+namespace {
+// Body shared by shard_prefill and shard_decode: validate, reserve pages,
+// enqueue, and only then commit the new lengths; any failure restores the page bookkeeping.
+int run_call(shard* s, const int32_t* seq_ids, int B, int T, bool decode, const void* x_in, void* x_out, void* hip_stream) {
+    SeqBatch sb;
+    int rc = check_batch(s, seq_ids, B, T, decode, &sb);
+    if (rc) return rc;
+    if (!x_in || !x_out) return fail(SHARD_E_INVAL, "null activation pointer");
+    rc = range_check(s);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    shard::Work* wk = nullptr;
+    rc = acquire_work(s, st, static_cast<size_t>(B) * T, &wk);
+    if (rc) return rc;
+    (void)hipGetLastError();   // a stale error of the caller's own must not be blamed on this call
+    GrowUndo undo(s, sb);
+    grow_sequences(s, sb, T, st);
+    if (decode) run_decode(s, *wk, sb, static_cast<const float*>(x_in), static_cast<float*>(x_out), st);
+    else run_prefill(s, *wk, sb, T, static_cast<const float*>(x_in), static_cast<float*>(x_out), st);
+    rc = release_work(wk, st);
+    if (rc == SHARD_OK) rc = check_launch();
+    if (rc) {
+        undo.rollback();
+        return rc;
+    }
+    for (int b = 0; b < B; ++b) s->seq_len[sb.seq[b]] += T;
+    return SHARD_OK;
+}
+
+// Nothing may throw across the C boundary: allocation failures of the host containers map to
+// SHARD_E_NOMEM, anything else to SHARD_E_HIP.
+template <typename F>
+int guarded(F&& body) {
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        return fail(SHARD_E_NOMEM, "host allocation failed");
+    } catch (const std::exception& e) {
+        return fail(SHARD_E_HIP, "unexpected failure: %s", e.what());
+    } catch (...) {
+        return fail(SHARD_E_HIP, "unexpected failure");
+    }
 }
 
 }  // namespace
@@ -487,8 +581,8 @@ extern "C" {
 
 const char* shard_last_error(void) { return g_err.c_str(); }
 
-int shard_create(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg* kv, int32_t layer_lo,
-                 int32_t layer_hi, const shard_layer_weights* w, int32_t weights_on_device) {
+static int create_impl(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg* kv, int32_t layer_lo,
+                       int32_t layer_hi, const shard_layer_weights* w, int32_t weights_on_device) {
     if (!out) return fail(SHARD_E_INVAL, "null out");
     *out = nullptr;
     int rc = validate_cfg(model, kv, layer_lo, layer_hi);
@@ -502,6 +596,10 @@ int shard_create(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg
     }
     shard* s = new (std::nothrow) shard();
     if (!s) return fail(SHARD_E_NOMEM, "host allocation failed");
+    struct Guard {   // every early return and every exception releases what was built so far
+        shard* s;
+        ~Guard() { if (s) free_all(s); }
+    } guard{s};
     s->m = *model;
     s->kv = *kv;
     s->layer_lo = layer_lo; s->layer_hi = layer_hi; s->L = L;
@@ -521,12 +619,15 @@ int shard_create(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg
 #define CREATE_TRY(expr)                                                                      \
     do {                                                                                      \
         hipError_t e_ = (expr);                                                               \
-        if (e_ != hipSuccess) {                                                               \
-            free_all(s);                                                                      \
+        if (e_ != hipSuccess)                                                                 \
             return fail(e_ == hipErrorOutOfMemory ? SHARD_E_NOMEM : SHARD_E_HIP, "%s: %s", #expr, \
                         hipGetErrorString(e_));                                               \
-        }                                                                                     \
     } while (0)
+
+    // the word the kernels raise when a value stored as half leaves half's range: pinned host
+    // memory mapped into the device, so the runtime reads it without a copy or a wait
+    CREATE_TRY(hipHostMalloc(reinterpret_cast<void**>(&s->oflow), sizeof(uint32_t), hipHostMallocMapped));
+    *s->oflow = 0u;
 
     const size_t page_elems = static_cast<size_t>(model->n_kv_heads) * kv->page_size * dh;
     uint32_t*& cvt_flag = s->cvt_flag;  // owned by the shard, so every failure path releases it
@@ -627,14 +728,21 @@ int shard_create(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg
         (void)hipFree(cvt_flag);
         cvt_flag = nullptr;
         if (e1 != hipSuccess || over) {
-            free_all(s);
             return e1 != hipSuccess ? fail(SHARD_E_HIP, "reading the conversion flag: %s", hipGetErrorString(e1))
                                     : fail(SHARD_E_INVAL, "a bf16 weight (times its RMSNorm gain, for wq/wk/wv/w_gate/w_up) exceeds the range of IEEE half (65504)");
         }
     }
 #undef CREATE_TRY
+    const int rc_l = check_launch();   // the conversion kernels of this create
+    if (rc_l) return rc_l;
+    guard.s = nullptr;
     *out = s;
     return SHARD_OK;
+}
+
+int shard_create(shard_t** out, const shard_model_cfg* model, const shard_kv_cfg* kv, int32_t layer_lo,
+                 int32_t layer_hi, const shard_layer_weights* w, int32_t weights_on_device) {
+    return guarded([&] { return create_impl(out, model, kv, layer_lo, layer_hi, w, weights_on_device); });
 }
 
 int shard_destroy(shard_t* s) {
@@ -677,35 +785,19 @@ int32_t shard_seq_len(shard_t* s, int32_t seq_id) {
 
 int shard_prefill(shard_t* s, const int32_t* seq_ids, int32_t B, int32_t T, const void* x_in, void* x_out,
                   void* hip_stream) {
-    SeqBatch sb;
-    int rc = check_batch(s, seq_ids, B, T, false, &sb);
-    if (rc) return rc;
-    if (!x_in || !x_out) return fail(SHARD_E_INVAL, "null activation pointer");
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    shard::Work* wk = nullptr;
-    rc = acquire_work(s, st, static_cast<size_t>(B) * T, &wk);
-    if (rc) return rc;
-    grow_sequences(s, sb, T, st);
-    run_prefill(s, *wk, sb, T, static_cast<const float*>(x_in), static_cast<float*>(x_out), st);
-    for (int b = 0; b < B; ++b) s->seq_len[sb.seq[b]] += T;
-    rc = release_work(wk, st);
-    return rc ? rc : check_launch();
+    return guarded([&] { return run_call(s, seq_ids, B, T, false, x_in, x_out, hip_stream); });
 }
 
 int shard_decode(shard_t* s, const int32_t* seq_ids, int32_t B, const void* x_in, void* x_out, void* hip_stream) {
-    SeqBatch sb;
-    int rc = check_batch(s, seq_ids, B, 1, true, &sb);
-    if (rc) return rc;
-    if (!x_in || !x_out) return fail(SHARD_E_INVAL, "null activation pointer");
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    shard::Work* wk = nullptr;
-    rc = acquire_work(s, st, static_cast<size_t>(B), &wk);
-    if (rc) return rc;
-    grow_sequences(s, sb, 1, st);
-    run_decode(s, *wk, sb, static_cast<const float*>(x_in), static_cast<float*>(x_out), st);
-    for (int b = 0; b < B; ++b) s->seq_len[sb.seq[b]] += 1;
-    rc = release_work(wk, st);
-    return rc ? rc : check_launch();
+    return guarded([&] { return run_call(s, seq_ids, B, 1, true, x_in, x_out, hip_stream); });
+}
+
+int shard_overflow(shard_t* s, int32_t clear, int32_t* overflowed) {
+    if (!s || !overflowed) return fail(SHARD_E_INVAL, "null argument");
+    volatile uint32_t* flag = s->oflow;
+    *overflowed = flag && *flag ? 1 : 0;
+    if (clear && flag) *flag = 0u;
+    return SHARD_OK;
 }
 
 int shard_timing_enable(shard_t* s, int32_t on) {
@@ -738,7 +830,7 @@ int shard_timing_read(shard_t* s, int64_t launches[SHARD_K_COUNT], double second
     return SHARD_OK;
 }
 
-int shard_profile(shard_t* s, int32_t B, int32_t T_prefill, int32_t n_decode, int32_t iters, shard_layer_profile* out) {
+static int profile_impl(shard_t* s, int32_t B, int32_t T_prefill, int32_t n_decode, int32_t iters, shard_layer_profile* out) {
     if (!s || !out) return fail(SHARD_E_INVAL, "null argument");
     if (B < 1 || B > SHARD_MAX_BATCH || T_prefill < 1 || n_decode < 0 || iters < 1)
         return fail(SHARD_E_INVAL, "bad profile shape");
@@ -808,6 +900,10 @@ int shard_profile(shard_t* s, int32_t B, int32_t T_prefill, int32_t n_decode, in
         p.kv_bytes_per_token = 2ull * m.n_kv_heads * m.head_dim * s->es;
     }
     return SHARD_OK;
+}
+
+int shard_profile(shard_t* s, int32_t B, int32_t T_prefill, int32_t n_decode, int32_t iters, shard_layer_profile* out) {
+    return guarded([&] { return profile_impl(s, B, T_prefill, n_decode, iters, out); });
 }
 
 // ---- the ends of a model: embedding lookup, final norm + LM head, greedy choice ----------
@@ -886,7 +982,7 @@ int shard_ends_create(shard_ends_t** out, const shard_model_cfg* model, int32_t 
 #undef ENDS_TRY
     if (over) {
         free_ends(e);
-        return fail(SHARD_E_INVAL, "a bf16 weight (times its RMSNorm gain, for wq/wk/wv/w_gate/w_up) exceeds the range of IEEE half (65504)");
+        return fail(SHARD_E_INVAL, "a bf16 entry of tok_embeddings or lm_head exceeds the range of IEEE half (65504)");
     }
     *out = e;
     return SHARD_OK;
@@ -946,5 +1042,50 @@ int shard_ends_argmax(shard_ends_t* e, const void* logits, int32_t n, int32_t* t
     launch_argmax(static_cast<const float*>(logits), n, e->vocab, token_ids_out, static_cast<hipStream_t>(hip_stream));
     return check_launch();
 }
+
+}  // extern "C"
+
+// ---- introspection of launch decisions (include/shard_introspect.h) -----------------------
+extern "C" {
+
+const char* shard_variant_name(int32_t family, int32_t index) {
+    switch (family) {
+        case SHARD_FAMILY_PREFILL_GEMM: return shk::prefill_gemm_variant_name(index);
+        case SHARD_FAMILY_DECODE_STREAM: return shk::decode_linear_variant_name(index);
+        case SHARD_FAMILY_DECODE_MFMA: return shk::decode_linear_mfma_variant_name(index);
+        default: return nullptr;
+    }
+}
+
+int32_t shard_variant_prefill_gemm(int32_t weight_dtype, int32_t M, int32_t N, int32_t K, int32_t residual_epilogue,
+                                   int32_t* k_slices) {
+    if ((weight_dtype != SHARD_F32 && weight_dtype != SHARD_BF16) || M < 1 || N < 1 || K < 1) return -1;
+    int ks = 1;
+    // O and down projections carry the shard's split-K scratch; QKV and gate/up never split
+    const int id = shk::choose_prefill_gemm(weight_dtype == SHARD_F32 ? DT_F32 : DT_F16, M, N, K,
+                                            residual_epilogue ? EPI_RESID : EPI_SWIGLU, residual_epilogue != 0, SPLITK_FLOATS, &ks);
+    if (k_slices) *k_slices = ks;
+    return id;
+}
+
+int32_t shard_variant_decode_linear(const shard_model_cfg* model, int32_t B, int32_t N, int32_t K, int32_t* family,
+                                    int32_t* rows_per_pass, int32_t* rows_per_workgroup) {
+    if (!model || !family || !rows_per_pass || !rows_per_workgroup || B < 1 || B > SHARD_MAX_BATCH || N < 1 || K < 1) return -1;
+    if (model->weight_dtype != SHARD_F32 && model->weight_dtype != SHARD_BF16) return -1;
+    if (decode_on_matrix_cores(*model, B)) {
+        int rows = 0;
+        const int id = shk::choose_decode_linear_mfma(N, K, &rows);
+        *family = SHARD_FAMILY_DECODE_MFMA;
+        *rows_per_pass = B < 16 ? B : 16;
+        *rows_per_workgroup = rows;
+        return id;
+    }
+    *family = SHARD_FAMILY_DECODE_STREAM;
+    *rows_per_pass = B < 8 ? B : 8;
+    *rows_per_workgroup = 0;
+    return shk::choose_decode_linear(model->weight_dtype == SHARD_F32 ? DT_F32 : DT_F16, *rows_per_pass, N, K);
+}
+
+void shard_test_inject_launch_error(int32_t on) { shk::inject_kernel_attribute_error(on != 0); }
 
 }  // extern "C"

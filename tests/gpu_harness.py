@@ -8,6 +8,11 @@ from oracle import llama_shard as orc
 from paper_2405_14371_amd import synth
 
 TOL = {"f32": 1e-3, "bf16": 2e-2}     # max |y - y_ref| / max |y_ref| on hidden states
+# The stricter companion: max_i |y_i - y_ref_i| / max(|y_ref_i|, rms(y_ref)).  Its bound is four
+# times the primary one: the largest of the d >= 128 roughly Gaussian elements of a hidden-state
+# row is about four times their rms, so an absolute error that meets the primary bound at the
+# largest element is up to four times larger relative to the rms floor.
+STRICT_TOL = {k: 4.0 * v for k, v in TOL.items()}
 
 
 def torch_mod():
@@ -33,9 +38,10 @@ def to_dev(a):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
 
 
-def run_gpu(shard, seq_ids, chunks):
-    """chunks: list of [B, T, d] float32 arrays; T == 1 chunks after the first go through
-    shard_decode, everything else through shard_prefill.  Returns list of outputs."""
+def run_gpu(shard, seq_ids, chunks, n_prefill=None):
+    """chunks: list of [B, T, d] float32 arrays.  The first n_prefill chunks go through
+    shard_prefill and the rest through shard_decode; without n_prefill, T == 1 chunks after
+    the first are decode steps and everything else is prefill.  Returns list of outputs."""
     torch = torch_mod()
     outs = []
     for i, x in enumerate(chunks):
@@ -43,7 +49,7 @@ def run_gpu(shard, seq_ids, chunks):
         yd = torch.empty_like(xd)
         B, T, _ = x.shape
         st = torch.cuda.current_stream().cuda_stream
-        if T == 1 and i > 0:
+        if (i >= n_prefill) if n_prefill is not None else (T == 1 and i > 0):
             shard.decode(seq_ids, xd, yd, st)
         else:
             shard.prefill(seq_ids, T, xd, yd, st)
@@ -62,7 +68,16 @@ def run_oracle(cfg, layers, chunks):
 
 
 def assert_parity(got, want, tol, what=""):
+    """tol: "f32" / "bf16" (both metrics at their stated bounds), or a number: the bound of the
+    primary metric, with four times that for the strict one."""
+    primary = TOL[tol] if isinstance(tol, str) else float(tol)
+    strict = 4.0 * primary
     for i, (g, w) in enumerate(zip(got, want)):
         assert np.all(np.isfinite(g)), f"{what} chunk {i}: non-finite output"
         err = orc.max_rel_err(g, w)
-        assert err <= tol, f"{what} chunk {i}: max rel err {err:.3e} > {tol:.1e}"
+        assert err <= primary, f"{what} chunk {i}: max rel err {err:.3e} > {primary:.1e}"
+        # the call's output tensor is one sequence's [T, d] block: the oracle treats sequences one by one
+        for b in range(g.shape[0]) if g.ndim == 3 else [None]:
+            gb, wb = (g, w) if b is None else (g[b], w[b])
+            err_s = orc.max_rel_err_strict(gb, wb)
+            assert err_s <= strict, f"{what} chunk {i} seq {b}: strict rel err {err_s:.3e} > {strict:.1e}"

@@ -351,6 +351,22 @@ def test_max_rel_err_metric():
     assert orc.max_rel_err(np.array([1.0, -4.0, 0.2]), ref) == pytest.approx(0.05)
 
 
+def test_strict_rel_err_metric_hand_values():
+    """ref = (3, -4, 0, 1): rms = sqrt(26/4) = 2.5495...  Deviations (0.3, 0, 0.5, 0.2) are
+    measured against max(|ref|, rms) = (3, 4, rms, rms)."""
+    ref = np.array([3.0, -4.0, 0.0, 1.0])
+    rms = np.sqrt(26.0 / 4.0)
+    got = orc.max_rel_err_strict(np.array([3.3, -4.0, 0.5, 1.2]), ref)
+    assert got == pytest.approx(max(0.3 / 3.0, 0.5 / rms, 0.2 / rms))
+    assert got == pytest.approx(0.5 / rms)
+    assert orc.max_rel_err_strict(ref, ref) == 0.0
+    # an error on a large element counts against that element, not against the rms
+    assert orc.max_rel_err_strict(np.array([3.0, -4.4, 0.0, 1.0]), ref) == pytest.approx(0.1)
+    # never looser than the primary metric
+    y = ref + np.array([0.01, -0.02, 0.03, 0.0])
+    assert orc.max_rel_err_strict(y, ref) >= orc.max_rel_err(y, ref)
+
+
 # --------------------------------------------------------------------------------------
 # Planted mistakes: each plausible slip must be caught by the brute-force pin.
 # --------------------------------------------------------------------------------------

@@ -137,3 +137,62 @@ def test_planner_rejects_bad_arguments(lib):
     assert e.value.code == -2
     assert lib.load().shard_plan_latency(None, None, None) == -1
     assert lib.load().shard_plan_throughput(None, 0, None, None) == -1
+
+
+# --------------------------------------------------------------------------------------
+# From a plan to pipeline stages (the compute and link terms of Eq. 9, Eq. 1)
+# --------------------------------------------------------------------------------------
+def test_oracle_stages_hand_worked_five_layers():
+    """Plan (0, 0, 2, 2, 1) over three devices, worked by hand:
+    stage times are column sums over the runs, the two links carry the activations of layers
+    1 and 3, the token returns from device 1 to device 0."""
+    tp = [[1, 9, 9], [2, 9, 9], [9, 9, 3], [9, 9, 4], [9, 5, 9]]
+    td = [[.1, 9, 9], [.2, 9, 9], [9, 9, .3], [9, 9, .4], [9, .5, 9]]
+    ap, ad = [10, 20, 30, 40, 50], [1, 2, 3, 4, 5]
+    bw = [[0, 7, 4], [5, 0, 7], [7, 8, 0]]
+    st = orc.stages_of((0, 0, 2, 2, 1), tp, td, ap, ad, bw)
+    assert st["stages"] == [0, 2, 1]
+    assert st["t_prefill"] == [3, 7, 5]
+    assert st["t_decode"] == pytest.approx([0.3, 0.7, 0.5])
+    assert st["c_prefill"] == pytest.approx([20 / 4, 40 / 8])
+    assert st["c_decode"] == pytest.approx([2 / 4, 4 / 8])
+    assert st["c_return"] == pytest.approx(5 / 5)
+    with pytest.raises(ValueError):
+        orc.stages_of((0, 1, 0), tp[:3], td[:3], ap[:3], ad[:3], bw)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_stages_agree_with_the_stage_time_of_eq9(lib, seed):
+    """max over stages of max(compute, incoming link) read off the collapsed stages is Eq. 9-10's
+    slowest stage, which the enumeration oracle computes directly from the plan; and the
+    library's shard_plan_to_stages returns what the oracle's stages_of does."""
+    rng = np.random.default_rng(100 + seed)
+    N, M = int(rng.integers(3, 9)), int(rng.integers(2, 5))
+    tdec = rng.uniform(0.1, 1.0, (N, M)); tpre = rng.uniform(1.0, 5.0, (N, M))
+    act = rng.uniform(1.0, 4.0, N); bw = rng.uniform(2.0, 20.0, (M, M))
+    prob = dict(t_comp=tdec, act_bytes=act, req_bytes=np.ones(N), mem_bytes=np.full(M, N / 2 + 0.5), bandwidth=bw)
+    _, dev = lib.plan_throughput(prob)
+    want = orc.stages_of(dev, tpre, tdec, 8 * act, act, bw)
+    got = lib.stages_of_plan(dev, tpre, tdec, 8 * act, act, bw)
+    assert got["stages"] == want["stages"]
+    for k in ("t_prefill", "t_decode", "c_prefill", "c_decode"):
+        assert got[k] == pytest.approx(want[k], rel=1e-12), k
+    assert got["c_return"] == pytest.approx(want["c_return"], rel=1e-12)
+    slowest = max(max(t, c) for t, c in zip(want["t_decode"], [0.0] + want["c_decode"]))
+    assert slowest == pytest.approx(orc.stage_time_of(prob, dev))
+    assert max(slowest, want["c_return"]) == pytest.approx(orc.stage_time_of(prob, dev, with_return_hop=True))
+
+
+def test_plan_to_stages_rejects_what_is_not_a_pipeline(lib):
+    tp = np.ones((3, 2)); act = np.ones(3); bw = np.ones((2, 2))
+    with pytest.raises(lib.ShardError) as e:
+        lib.stages_of_plan([0, 1, 0], tp, tp, act, act, bw)      # device 0 owns two ranges
+    assert e.value.code == -2
+    with pytest.raises(lib.ShardError) as e:
+        lib.stages_of_plan([0, 2, 2], tp, tp, act, act, bw)      # device index outside [0, M)
+    assert e.value.code == -1
+    with pytest.raises(lib.ShardError) as e:
+        lib.stages_of_plan([0, 1, 1], tp, tp, act, act, np.zeros((2, 2)))   # a used link without bandwidth
+    assert e.value.code == -1
+    one = lib.stages_of_plan([0, 0, 0], tp, 2 * tp, act, act, bw)
+    assert one == dict(stages=[0], t_prefill=[3.0], t_decode=[6.0], c_prefill=[], c_decode=[], c_return=0.0)
