@@ -15,6 +15,8 @@ inputs are resident in HBM before the timed region.  Prints one JSON line.
                    events attached to each of its dispatches (they read the kernel's own start
                    and end, as a profiler's kernel trace does), in one extra instrumented step
   cpu_baseline     the float64 CPU oracle timed on a bounded sample of the same workload
+  also             the other BASELINE.json configurations (7B 32 layers bf16; 13B eight micro-batches;
+                   70B batch 16), one timed step each after one warm-up step, same fields
 """
 from __future__ import annotations
 
@@ -69,15 +71,19 @@ def algorithmic_work(cfg, wl):
 
 
 def cpu_baseline(cfg, wl, seed):
-    """Time the oracle, as it stands, on a bounded sample (10-20 s of host work at the 7B
-    shape): 2 layers of the workload's layer shape, a 128-token prefill and 64 decode steps;
-    scale per-layer times to the shard."""
+    """Time the oracle, as it stands, on a bounded sample of the workload (about 20-30 s of host
+    work at the 7B shape): as many of the shard's layers as fit 16 GB of float64 copies (all 8 of
+    the default workload, so nothing is extrapolated there), a 64-token prefill and 16 decode
+    steps; per-layer times are scaled only if layers had to be left out."""
     from threadpoolctl import threadpool_info
     from oracle import llama_shard as orc
     from paper_2405_14371_amd import synth
-    n_l, t_pre, n_dec = min(2, wl["layers"]), min(128, wl["T"]), min(64, wl["n_dec"])
+    per_layer_f64 = orc.params_per_layer(cfg) * 8
+    n_l = max(1, min(wl["layers"], int(16e9 // per_layer_f64)))
+    t_pre, n_dec = min(64, wl["T"]), min(16, wl["n_dec"])
     layers = synth.shard_weights(cfg, seed, 0, n_l, wl["dtype"])
     o = orc.OracleShard(cfg, layers, keep_f64=True)
+    del layers
     x = synth.hidden_states(cfg, seed, "prefill", 0, 0, 1, t_pre)[0].astype(np.float64)
     t0 = time.perf_counter()
     o.forward(0, x)
@@ -90,34 +96,55 @@ def cpu_baseline(cfg, wl, seed):
     scale = wl["layers"] / n_l
     return {
         "value": round(wl["B"] / (t_dec * scale), 4), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-        "sample": f"{n_l} of {wl['layers']} layers of the workload's shape, {t_pre}-token prefill + {n_dec} decode "
-                  f"steps, batch 1; per-layer decode-step time scaled to {wl['layers']} layers",
+        "sample": f"{n_l} of {wl['layers']} layers of the workload, {t_pre}-token prefill + {n_dec} decode steps, batch 1"
+                  + ("" if n_l == wl["layers"] else f"; per-layer times scaled to {wl['layers']} layers"),
         "prefill_tokens_per_s": round(t_pre / (t_prefill * scale), 3),
     }
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS))
-    ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs one shard on ONE GPU; --gpus > 1 is not supported "
-              "(a shard is a single device's share of the pipeline)", file=sys.stderr)
-        sys.exit(2)
+ARITHMETIC = {   # what the path computes in (not a precision claim)
+    "f32": "f32",
+    "bf16": "f16 (bf16 weights converted once to IEEE half; f16 MFMA / FMA inputs, f32 accumulation and residual stream)",
+}
+# the other benchmark configurations that ride along on the default run, each with fewer steps
+ALSO_DEFAULT = ("llama2-7b-32l-bf16-b1-p1024-d256", "llama2-13b-l0-19-bf16-8xb1-p256-d128",
+                "llama2-70b-l0-19-bf16-b16-p512-d128")
 
-    import torch
-    import paper_2405_14371_amd as pkg
-    from paper_2405_14371_amd import synth
-    lib = pkg.binding
-    lib.load()
-    torch.cuda.set_device(0)
 
-    wl = WORKLOADS[args.workload]
+def prefill_roof(cfg, wl, work):
+    """The binding roof of ONE shard_prefill call of the workload: the larger of its MFMA time
+    (algorithmic FLOPs at the dtype's peak) and its HBM time (every weight once, the boundary
+    activations in and out, the KV cache written once) - a prefill of few rows (config 4's
+    256-token micro-batches) is bandwidth-bound."""
+    B, T, L = wl["B"], wl["T"], wl["layers"]
+    e = 4 if wl["dtype"] == "f32" else 2
+    kv_tok = 2 * cfg["n_kv_heads"] * cfg["head_dim"] * e
+    t_mfma = work["prefill_flops"] / (MFMA_PEAK_TFLOPS[wl["dtype"]] * 1e12)
+    t_hbm = (work["weight_bytes"] + 2 * B * T * cfg["d_model"] * 4 + B * T * L * kv_tok) / (HBM_PEAK_GBPS * 1e9)
+    return ("mfma" if t_mfma >= t_hbm else "hbm"), max(t_mfma, t_hbm), t_mfma, t_hbm
+
+
+def stored_traffic(lib, cfg, wl, workload, wd):
+    """HBM bytes per launch of the dominant decode kernel from a stored rocprofv3 PMC summary
+    (profiles/pmc_traffic.json), or None with the reason.  The entry names the kernel variants
+    it was measured on; it is used only if this run launches exactly those."""
+    d, hq, hkv, dh, F = (cfg[k] for k in ("d_model", "n_heads", "n_kv_heads", "head_dim", "ffn_dim"))
+    shapes = (((hq + 2 * hkv) * dh, d), (d, hq * dh), (2 * F, d), (d, F))
+    now = sorted({lib.variant_decode_linear(cfg, wd, wl["B"], n, k)[0] for n, k in shapes})
+    try:
+        with open(os.path.join(ROOT, "profiles", "pmc_traffic.json")) as fh:
+            entry = json.load(fh)[workload]
+    except (OSError, KeyError, ValueError):
+        return None, "no stored PMC summary for this workload", now
+    if sorted(entry.get("kernel_variants", [])) != now:
+        return None, f"stored PMC summary ({entry.get('source')}) is for other kernel variants: stale", now
+    return entry["traffic_bytes_per_launch"], f"stored: {entry.get('source')}", now
+
+
+def measure(lib, torch, synth, workload, steps, warmup, seed, with_cpu_baseline):
+    """Build the workload's shard, time `steps` steps after `warmup`, run one instrumented step,
+    release everything.  Returns the fields of the JSON line for this workload."""
+    wl = WORKLOADS[workload]
     cfg = synth.model_cfg(wl["model"])
     work = algorithmic_work(cfg, wl)
     wd = lib.SHARD_F32 if wl["dtype"] == "f32" else lib.SHARD_BF16
@@ -125,15 +152,15 @@ def main():
     MB = wl.get("micro", 1)     # micro-batches driven round-robin through the shard (each of batch B)
 
     t0 = time.perf_counter()
-    layers = [lib.pack_layers([synth.layer_weights(cfg, args.seed, li, wl["dtype"])], wd)[0] for li in range(L)]
+    layers = [lib.pack_layers([synth.layer_weights(cfg, seed, li, wl["dtype"])], wd)[0] for li in range(L)]
     sh = lib.Shard(cfg, layers, 0, weight_dtype=wd, max_seqs=B * MB, max_seq_len=T + n_dec,
                    page_size=16, max_batch_tokens=B * T)
     del layers
     x_pre = torch.from_numpy(np.stack([np.concatenate(
-        [synth.hidden_states(cfg, args.seed, "prefill", 0, mb * B + b, 1, T) for b in range(B)])
+        [synth.hidden_states(cfg, seed, "prefill", 0, mb * B + b, 1, T) for b in range(B)])
         for mb in range(MB)])).cuda()                         # [MB, B, T, d]
     x_dec = torch.from_numpy(np.stack([np.stack(
-        [np.concatenate([synth.hidden_states(cfg, args.seed, "dec", s, mb * B + b, 1, 1) for b in range(B)])
+        [np.concatenate([synth.hidden_states(cfg, seed, "dec", s, mb * B + b, 1, 1) for b in range(B)])
          for mb in range(MB)]) for s in range(n_dec)])).cuda()   # [n_dec, MB, B, 1, d]
     y_pre = torch.empty_like(x_pre)
     y_dec = torch.empty_like(x_dec)
@@ -174,20 +201,21 @@ def main():
                 sh.seq_free(i)
         return (e0.elapsed_time(e1) * 1e-3, e1.elapsed_time(e2) * 1e-3) if timed else None
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         one_step(False)
     torch.cuda.synchronize()
     t_wall0 = time.perf_counter()
-    times = [one_step(True) for _ in range(args.steps)]
+    times = [one_step(True) for _ in range(steps)]
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_wall0
     assert torch.isfinite(y_dec).all() and torch.isfinite(y_pre).all()
+    assert not sh.overflow()
 
     t_pre = sum(t[0] for t in times)
     t_dec = sum(t[1] for t in times)
-    dec_tok_s = MB * B * n_dec * args.steps / t_dec
-    dec_gbps = work["decode_bytes"] * MB * n_dec * args.steps / t_dec / 1e9
-    pre_tflops = work["prefill_flops"] * MB * args.steps / t_pre / 1e12
+    dec_tok_s = MB * B * n_dec * steps / t_dec
+    dec_gbps = work["decode_bytes"] * MB * n_dec * steps / t_dec / 1e9
+    pre_tflops = work["prefill_flops"] * MB * steps / t_pre / 1e12
 
     # one more step with a HIP event pair on every dispatch, for the per-kernel roofline
     sh.timing_enable(True)
@@ -203,20 +231,14 @@ def main():
     lin = {f: sum(kt["decode_" + k][f] for k in proj) for f in ("launches", "seconds")}
     lin_bytes = sum(work["linear_bytes"].values()) * calls_dec
     lin_gbps = lin_bytes / lin["seconds"] / 1e9
-    # HBM bytes per launch from rocprofv3 PMC runs of this same command (FETCH_SIZE and
-    # WRITE_SIZE, scaled by what they read for a copy of known size); see profiles/
-    traffic = None
-    try:
-        with open(os.path.join(ROOT, "profiles", "pmc_traffic.json")) as fh:
-            traffic = json.load(fh)[args.workload]["decode_linear_kernel"]["traffic_bytes_per_launch"]
-    except (OSError, KeyError, ValueError):
-        pass
+    traffic, traffic_note, variants = stored_traffic(lib, cfg, wl, workload, wd)
     n_lin = 4 * calls_dec                   # projection launches (the batched path's one cast of x_in per step not counted)
     roofline = {
-        "kernel": ("decode_linear_mfma_kernel" if mfma_decode else "decode_linear_kernel")
+        "kernel": ("decode_linear_mfma_kernel / decode_linear_dma_kernel" if mfma_decode else "decode_linear_kernel")
                   + " (weight-streaming projections of shard_decode)",
+        "kernel_variants": variants,
         "bound": "hbm", "achieved": round(lin_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-        "frac": round(lin_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
+        "frac": round(lin_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic, "traffic_source": traffic_note,
         "launches": n_lin, "avg_launch_us": round(lin["seconds"] / n_lin * 1e6, 2),
         "algorithmic_bytes_per_launch": round(lin_bytes / n_lin),
     }
@@ -238,25 +260,77 @@ def main():
         kernel_seconds["prefill_" + k]["tflops"] = round(
             work["gemm_flops"][k] * calls_pre / kt["prefill_" + k]["seconds"] / 1e12, 2)
     sh.close()
+    del sh, x_pre, x_dec, y_pre, y_dec
+    torch.cuda.empty_cache()
 
+    bound, t_roof, t_mfma, t_hbm = prefill_roof(cfg, wl, work)
+    prefill_call_s = t_pre / (steps * MB)        # micro-batches overlap on two streams: the mean share of a call
     out = {
         "metric": "shard_decode_tokens_per_s",
-        "value": round(dec_tok_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round((t_pre + t_dec) / args.steps * 1e3, 3), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": wl["dtype"], "data": "synthetic",
-        "config": {"workload": args.workload, "layers": L, "batch": B, "micro_batches": MB, "decode_streams": max(1, len(side)),
+        "value": round(dec_tok_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": round((t_pre + t_dec) / steps * 1e3, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": ARITHMETIC[wl["dtype"]], "data": "synthetic",
+        "config": {"workload": workload, "layers": L, "batch": B, "micro_batches": MB, "decode_streams": max(1, len(side)),
                    "prefill_tokens": T,
-                   "decode_steps": n_dec, "page_size": 16, "seed": args.seed},
-        "decode_ms_per_step": round(t_dec / (n_dec * MB * args.steps) * 1e3, 4),
+                   "decode_steps": n_dec, "page_size": 16, "seed": seed, "weights": wl["dtype"]},
+        "decode_ms_per_step": round(t_dec / (n_dec * MB * steps) * 1e3, 4),
         "decode_gbps": round(dec_gbps, 1), "decode_hbm_frac": round(dec_gbps / HBM_PEAK_GBPS, 4),
-        "prefill_ms": round(t_pre / args.steps * 1e3, 3),
-        "prefill_tokens_per_s": round(MB * B * T * args.steps / t_pre, 1),
+        "prefill_ms": round(t_pre / steps * 1e3, 3),
+        "prefill_tokens_per_s": round(MB * B * T * steps / t_pre, 1),
         "prefill_tflops": round(pre_tflops, 2), "prefill_mfma_frac": round(pre_tflops / peak_tf, 4),
+        # one prefill call against its binding roof, max(MFMA time, HBM time)
+        "prefill_bound": {"bound": bound, "roof_ms_per_call": round(t_roof * 1e3, 4), "mfma_ms": round(t_mfma * 1e3, 4),
+                          "hbm_ms": round(t_hbm * 1e3, 4), "measured_ms_per_call": round(prefill_call_s * 1e3, 4),
+                          "frac": round(t_roof / prefill_call_s, 4)},
         "roofline": roofline, "roofline_prefill": roofline_prefill, "kernel_ms_instrumented_step": kernel_seconds,
         "wall_s_timed_region": round(wall, 3), "setup_s": round(setup_s, 1),
     }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, wl, args.seed)
+    if with_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, wl, seed)
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS))
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--also", default=None,
+                    help="comma-separated workloads measured after the main one with one timed step each and reported in "
+                         "the line's `also` array; 'none' for none; default: the other BASELINE configurations when the "
+                         "main workload is the default one")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs one shard on ONE GPU; --gpus > 1 is not supported "
+              "(a shard is a single device's share of the pipeline)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2405_14371_amd as pkg
+    from paper_2405_14371_amd import synth
+    lib = pkg.binding
+    lib.load()
+    torch.cuda.set_device(0)
+
+    if args.also is None:
+        also = ALSO_DEFAULT if args.workload == DEFAULT_WORKLOAD else ()
+    else:
+        also = tuple(w for w in args.also.split(",") if w and w != "none")
+    for w in also:
+        if w not in WORKLOADS:
+            ap.error(f"unknown workload in --also: {w}")
+    out = measure(lib, torch, synth, args.workload, args.steps, args.warmup, args.seed, not args.no_cpu_baseline)
+    keep = ("value", "unit", "steps", "warmup", "ms_per_step", "dtype", "config", "decode_ms_per_step", "decode_gbps",
+            "decode_hbm_frac", "prefill_ms", "prefill_tokens_per_s", "prefill_tflops", "prefill_mfma_frac", "prefill_bound",
+            "roofline", "roofline_prefill", "setup_s")
+    if also:
+        out["also"] = []
+        for w in also:
+            r = measure(lib, torch, synth, w, 1, 1, args.seed, False)
+            out["also"].append({k: r[k] for k in keep})
     print(json.dumps(out))
 
 
