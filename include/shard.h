@@ -31,7 +31,7 @@
  *    (the half copy of the residual stream, the SwiGLU output) and the KV cache are IEEE half,
  *    largest finite value 65504.  Every kernel that rounds such a value to half tests it; a
  *    value beyond the range (or a NaN) raises a sticky flag in host-visible memory, and from
- *    then on shard_prefill / shard_decode return SHARD_E_RANGE before
+ *    then on shard_prefill / shard_decode / shard_decode_static return SHARD_E_RANGE before
  *    they launch anything (the flag is seen once the offending kernel has run, so at the
  *    latest by the call after the caller's next synchronisation).  shard_overflow reads and
  *    optionally clears it.  The fp32 path has no such limit.
@@ -167,6 +167,23 @@ int shard_prefill(shard_t *s, const int32_t *seq_ids, int32_t B, int32_t T,
  * differ between sequences.  x_in, x_out: device pointers, float32 [B, d_model]. */
 int shard_decode(shard_t *s, const int32_t *seq_ids, int32_t B,
                  const void *x_in, void *x_out, void *hip_stream);
+
+/* shard_decode for callers that cannot allocate device memory or must know that no library
+ * call does: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same kernels and same results as shard_decode, but every
+ * intermediate buffer of the step (normalised activations, q, attention output and its
+ * context-slice partials, the SwiGLU output) is carved from one array of
+ * SHARD_STATIC_SCRATCH_BYTES that lives in the library's device image (one copy per GPU, held
+ * until the process ends) instead of the workspace shard_create allocated; the call makes no
+ * hipMalloc / hipFree and creates no events.  A step whose buffers would not fit
+ * (roughly B * (3 d_model + 2 Hq dh + ffn_dim) * 4 bytes plus the attention partials) is
+ * refused with SHARD_E_INVAL and a message that states both sizes; so is a call while
+ * shard_timing_enable is on (timing creates events).  All calls on one GPU, from any shard,
+ * share that array: calls that overlap on the device (different streams or shards) race -
+ * order them on one stream or with events.  Nothing in the array needs to start at zero. */
+#define SHARD_STATIC_SCRATCH_BYTES (8u << 20)
+int shard_decode_static(shard_t *s, const int32_t *seq_ids, int32_t B,
+                        const void *x_in, void *x_out, void *hip_stream);
 
 /* Whether a value rounded to IEEE half by this shard's kernels has left half's range since
  * the shard was created (or since the flag was last cleared): *overflowed = 0 or 1, for the

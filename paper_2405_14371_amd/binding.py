@@ -12,6 +12,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libshard.so")
 
 SHARD_OK, SHARD_E_INVAL, SHARD_E_NOMEM, SHARD_E_KV_FULL, SHARD_E_STATE, SHARD_E_HIP, SHARD_E_RANGE = 0, -1, -2, -3, -4, -5, -6
+SHARD_STATIC_SCRATCH_BYTES = 8 << 20
 SHARD_F32, SHARD_BF16 = 0, 1
 SHARD_MAX_BATCH = 64
 KERNEL_CLASSES = ("decode_qkv", "decode_attn", "decode_o", "decode_gateup", "decode_down", "prefill_norm",
@@ -33,7 +34,7 @@ class PipelineProblem(C.Structure):
 
 EXPORTS = (
     "shard_create", "shard_destroy", "shard_seq_alloc", "shard_seq_free", "shard_seq_len",
-    "shard_prefill", "shard_decode", "shard_overflow", "shard_profile",
+    "shard_prefill", "shard_decode", "shard_decode_static", "shard_overflow", "shard_profile",
     "shard_timing_enable", "shard_timing_read",
     "shard_last_error", "shard_plan_latency", "shard_plan_throughput", "shard_plan_to_stages", "shard_simulate_pipeline",
     "shard_ends_create", "shard_ends_destroy", "shard_ends_embed", "shard_ends_logits", "shard_ends_argmax",
@@ -94,6 +95,7 @@ def load():
     lib.shard_seq_len.argtypes = [vp, i32]
     lib.shard_prefill.argtypes = [vp, C.POINTER(i32), i32, i32, vp, vp, vp]
     lib.shard_decode.argtypes = [vp, C.POINTER(i32), i32, vp, vp, vp]
+    lib.shard_decode_static.argtypes = [vp, C.POINTER(i32), i32, vp, vp, vp]
     lib.shard_overflow.argtypes = [vp, i32, C.POINTER(i32)]
     lib.shard_profile.argtypes = [vp, i32, i32, i32, i32, C.POINTER(LayerProfile)]
     lib.shard_timing_enable.argtypes = [vp, i32]
@@ -213,6 +215,10 @@ class Shard:
     def decode(self, seq_ids, x_in, x_out, stream: int = 0) -> None:
         ids, n = _ids(seq_ids)
         _check(load().shard_decode(self._h, ids, n, _ptr(x_in), _ptr(x_out), stream))
+
+    def decode_static(self, seq_ids, x_in, x_out, stream: int = 0) -> None:
+        ids, n = _ids(seq_ids)
+        _check(load().shard_decode_static(self._h, ids, n, _ptr(x_in), _ptr(x_out), stream))
 
     def overflow(self, clear: bool = False) -> bool:
         out = C.c_int32(0)

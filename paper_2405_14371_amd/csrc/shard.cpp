@@ -108,6 +108,7 @@ struct shard {
     Timing timing;
     uint32_t* cvt_flag = nullptr;   // overflow flag of the bf16 -> half conversion during create
     uint32_t* oflow = nullptr;      // host-visible (pinned, mapped) word: a half store left half's range
+    void* static_scratch = nullptr; // this device's copy of the library's static scratch array
     std::vector<hipEvent_t> layer_ev;  // L+1 events, used by shard_profile
     bool record_layers = false;
 };
@@ -529,12 +530,79 @@ int range_check(const shard* s) {
     return SHARD_OK;
 }
 
+// Bytes of the static scratch array a decode step of this batch needs, and the carve-up.
+constexpr size_t SCRATCH_ALIGN = 256;
+size_t align_up(size_t v) { return (v + SCRATCH_ALIGN - 1) / SCRATCH_ALIGN * SCRATCH_ALIGN; }
+
+// Largest number of context slices any attention launch of this decode step uses (the launch
+// sequence of run_decode / run_decode_mfma decides the sub-batches).
+int max_nsplit_of_step(const shard* s, const SeqBatch& all) {
+    if (!decode_on_matrix_cores(s->m, all.n)) return pick_nsplit(s, all);
+    int worst = 1;
+    for (int b0 = 0; b0 < all.n; b0 += 16) {
+        SeqBatch sb;
+        sb.n = all.n - b0 < 16 ? all.n - b0 : 16;
+        for (int i = 0; i < sb.n; ++i) { sb.seq[i] = all.seq[b0 + i]; sb.pos[i] = all.pos[b0 + i]; }
+        const int n = pick_nsplit(s, sb);
+        worst = worst > n ? worst : n;
+    }
+    return worst;
+}
+
+int carve_static(const shard* s, const SeqBatch& sb, shard::Work* w) {
+    const size_t B = sb.n, d = s->m.d_model, nq = s->nq, F = s->m.ffn_dim, dh = s->m.head_dim;
+    const size_t nsplit = max_nsplit_of_step(s, sb);
+    const size_t units = B * s->m.n_heads;
+    const size_t sizes[6] = {B * d * sizeof(float), B * nq * sizeof(float), B * nq * sizeof(float), B * F * sizeof(float),
+                             units * nsplit * dh * sizeof(float), units * nsplit * 2 * sizeof(float)};
+    size_t off[6], total = 0;
+    for (int i = 0; i < 6; ++i) { off[i] = total; total += align_up(sizes[i]); }
+    if (total > SHARD_STATIC_SCRATCH_BYTES)
+        return fail(SHARD_E_INVAL, "this decode step needs %zu bytes of scratch; shard_decode_static has %u (use shard_decode)",
+                    total, SHARD_STATIC_SCRATCH_BYTES);
+    char* base = static_cast<char*>(s->static_scratch);
+    w->h = base + off[0];
+    w->q = reinterpret_cast<float*>(base + off[1]);
+    w->o = base + off[2];
+    w->f = base + off[3];
+    w->part_o = reinterpret_cast<float*>(base + off[4]);
+    w->part_ml = reinterpret_cast<float*>(base + off[5]);
+    w->splitk = nullptr;
+    w->rows = B;
+    return SHARD_OK;
+}
+
 }  // namespace
 
+// Scratch of shard_decode_static: part of the library's device image, so no call ever allocates
+// it.  In host code this name is only a handle for hipGetSymbolAddress - the address kernels get
+// is the one that call returns, looked up once per device in shard_create.
+static __device__ __align__(256) unsigned char scratch[SHARD_STATIC_SCRATCH_BYTES];
+
 namespace {
-// Body shared by shard_prefill and shard_decode: validate, reserve pages,
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {nullptr};
+
+int static_scratch_of_current_device(void** out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(SHARD_E_HIP, "device ordinal %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(SHARD_E_HIP, "hipGetSymbolAddress returned a null address for the static scratch array");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SHARD_OK;
+}
+
+// Body shared by shard_prefill, shard_decode and shard_decode_static: validate, reserve pages,
 // enqueue, and only then commit the new lengths; any failure restores the page bookkeeping.
-int run_call(shard* s, const int32_t* seq_ids, int B, int T, bool decode, const void* x_in, void* x_out, void* hip_stream) {
+int run_call(shard* s, const int32_t* seq_ids, int B, int T, bool decode, bool static_ws, const void* x_in, void* x_out,
+             void* hip_stream) {
     SeqBatch sb;
     int rc = check_batch(s, seq_ids, B, T, decode, &sb);
     if (rc) return rc;
@@ -542,15 +610,24 @@ int run_call(shard* s, const int32_t* seq_ids, int B, int T, bool decode, const 
     rc = range_check(s);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    shard::Work local{};
     shard::Work* wk = nullptr;
-    rc = acquire_work(s, st, static_cast<size_t>(B) * T, &wk);
-    if (rc) return rc;
+    if (static_ws) {
+        if (s->timing.on) return fail(SHARD_E_STATE, "shard_decode_static cannot run while kernel timing is enabled (it creates events)");
+        if (s->record_layers) return fail(SHARD_E_STATE, "shard_decode_static cannot run inside shard_profile");
+        rc = carve_static(s, sb, &local);
+        if (rc) return rc;
+        wk = &local;
+    } else {
+        rc = acquire_work(s, st, static_cast<size_t>(B) * T, &wk);
+        if (rc) return rc;
+    }
     (void)hipGetLastError();   // a stale error of the caller's own must not be blamed on this call
     GrowUndo undo(s, sb);
     grow_sequences(s, sb, T, st);
     if (decode) run_decode(s, *wk, sb, static_cast<const float*>(x_in), static_cast<float*>(x_out), st);
     else run_prefill(s, *wk, sb, T, static_cast<const float*>(x_in), static_cast<float*>(x_out), st);
-    rc = release_work(wk, st);
+    rc = static_ws ? SHARD_OK : release_work(wk, st);
     if (rc == SHARD_OK) rc = check_launch();
     if (rc) {
         undo.rollback();
@@ -628,6 +705,10 @@ static int create_impl(shard_t** out, const shard_model_cfg* model, const shard_
     // memory mapped into the device, so the runtime reads it without a copy or a wait
     CREATE_TRY(hipHostMalloc(reinterpret_cast<void**>(&s->oflow), sizeof(uint32_t), hipHostMallocMapped));
     *s->oflow = 0u;
+    {
+        const int rc_s = static_scratch_of_current_device(&s->static_scratch);
+        if (rc_s) return rc_s;
+    }
 
     const size_t page_elems = static_cast<size_t>(model->n_kv_heads) * kv->page_size * dh;
     uint32_t*& cvt_flag = s->cvt_flag;  // owned by the shard, so every failure path releases it
@@ -785,11 +866,15 @@ int32_t shard_seq_len(shard_t* s, int32_t seq_id) {
 
 int shard_prefill(shard_t* s, const int32_t* seq_ids, int32_t B, int32_t T, const void* x_in, void* x_out,
                   void* hip_stream) {
-    return guarded([&] { return run_call(s, seq_ids, B, T, false, x_in, x_out, hip_stream); });
+    return guarded([&] { return run_call(s, seq_ids, B, T, false, false, x_in, x_out, hip_stream); });
 }
 
 int shard_decode(shard_t* s, const int32_t* seq_ids, int32_t B, const void* x_in, void* x_out, void* hip_stream) {
-    return guarded([&] { return run_call(s, seq_ids, B, 1, true, x_in, x_out, hip_stream); });
+    return guarded([&] { return run_call(s, seq_ids, B, 1, true, false, x_in, x_out, hip_stream); });
+}
+
+int shard_decode_static(shard_t* s, const int32_t* seq_ids, int32_t B, const void* x_in, void* x_out, void* hip_stream) {
+    return guarded([&] { return run_call(s, seq_ids, B, 1, true, true, x_in, x_out, hip_stream); });
 }
 
 int shard_overflow(shard_t* s, int32_t clear, int32_t* overflowed) {
