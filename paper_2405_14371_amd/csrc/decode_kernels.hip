@@ -16,8 +16,8 @@ namespace shk {
 // lane are in flight.  Partial sums are reduced across the wave with shuffles, across the
 // four waves through LDS, always in the same order.
 // ---------------------------------------------------------------------------------------
-template <typename WT, int NB, int R, int U, bool ROT = false>
-__global__ __launch_bounds__(256) void decode_linear_kernel(DecodeLinear a, SeqBatch sb) {
+template <typename WT, int NB, int R, int U, bool ROT = false, int THREADS = 256>
+__global__ __launch_bounds__(THREADS) void decode_linear_kernel(DecodeLinear a, SeqBatch sb) {
     constexpr int VEC = Elem<WT>::VEC;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int row0 = blockIdx.x * R;
@@ -25,14 +25,14 @@ __global__ __launch_bounds__(256) void decode_linear_kernel(DecodeLinear a, SeqB
     // ROT: every workgroup starts its walk over K at its own 4 KB iteration.  With long rows
     // (K = 11008) this spreads the workgroups of a launch over the memory channels (+3..7 %);
     // with K = 4096 it gains nothing and costs a few instructions, so it is opt-in per shape.
-    const int iters = (nchunk + 255) / 256;
-    const int rot = ROT ? static_cast<int>((blockIdx.x * 5u) % static_cast<unsigned>(iters)) * 256 : 0;
+    constexpr int WAVES = THREADS / 64;
+    const int iters = (nchunk + THREADS - 1) / THREADS;
+    const int rot = ROT ? static_cast<int>((blockIdx.x * 5u) % static_cast<unsigned>(iters)) * THREADS : 0;
     const WT* __restrict__ W = static_cast<const WT*>(a.W);
     const bool norm = a.gain != nullptr;
 
-    __shared__ float s_red[4][R * NB];
-    __shared__ float s_ssq[4][NB];
-    __shared__ float s_val[R * NB];
+    __shared__ float s_red[WAVES][R * NB];
+    __shared__ float s_ssq[WAVES][NB];
 
     float acc[R][NB];
     float ssq[NB];
@@ -50,13 +50,41 @@ __global__ __launch_bounds__(256) void decode_linear_kernel(DecodeLinear a, SeqB
         rowp[r] = W + static_cast<size_t>(n) * a.K;
     }
 
-    for (int c0 = tid; c0 < nchunk; c0 += 256 * U) {
+    // What the epilogue needs from memory is fetched NOW, by the threads that will run it, so that
+    // the end of the workgroup is arithmetic and stores only: with every workgroup of a launch
+    // resident at once they all finish together, and a chain of dependent loads there (residual;
+    // position -> rotation table; block table -> page) was 1.6 - 3.3 us of every launch.
+    typedef typename ActOf<WT>::type CT;  // cache element type
+    float pre_resid = 0.f;                // EPI_RESID: the residual element of (row tid / NB, activation row tid % NB)
+    float2 pre_cs = make_float2(1.f, 0.f);  // EPI_QKV: (cos, sin) of the pair this thread rotates
+    size_t pre_at = 0;                    // EPI_QKV: element offset of the pair in the K or V pool
+    if (a.epi == EPI_RESID) {
+        if (tid < R * NB) {
+            const int r = tid / NB, b = tid % NB, n = row0 + r;
+            if (n < a.N && b < a.nb) pre_resid = a.resid[static_cast<size_t>(b) * a.N + n];
+        }
+    } else if (a.epi == EPI_QKV) {
+        if (tid < (R / 2) * NB) {
+            const int j = tid / NB, b = tid % NB, n0 = row0 + 2 * j;
+            if (n0 < a.N && b < a.nb) {
+                const int dh = a.kv.dh, nq = a.hq * dh, nk = a.kv.hkv * dh;
+                const int pos = sb.pos[b], e = n0 % dh;
+                if (n0 < nq + nk) pre_cs = a.rope[static_cast<size_t>(pos) * (dh / 2) + e / 2];
+                if (n0 >= nq) {
+                    const int hk = (n0 - nq - (n0 < nq + nk ? 0 : nk)) / dh;
+                    pre_at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
+                }
+            }
+        }
+    }
+
+    for (int c0 = tid; c0 < nchunk; c0 += THREADS * U) {
         Vec16<WT> w[U][R];
         int cc[U];
         bool ok[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int c = c0 + 256 * u;
+            const int c = c0 + THREADS * u;
             ok[u] = c < nchunk;
             cc[u] = ok[u] ? c : c0;
             if constexpr (ROT) {  // walk K from a per-workgroup offset (a rotation of the chunk index)
@@ -112,35 +140,48 @@ __global__ __launch_bounds__(256) void decode_linear_kernel(DecodeLinear a, SeqB
     for (int r = 0; r < R; ++r)
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            const float v = wave_sum(acc[r][b]);
+            const float v = wave_sum_rows(acc[r][b]);
             if (lane == 0) s_red[wave][r * NB + b] = v;
         }
     if (norm) {
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            const float v = wave_sum(ssq[b]);
+            const float v = wave_sum_rows(ssq[b]);
             if (lane == 0) s_ssq[wave][b] = v;
         }
     }
     __syncthreads();
-    if (tid < R * NB) {
-        float v = (s_red[0][tid] + s_red[1][tid]) + (s_red[2][tid] + s_red[3][tid]);
+    // element idx = row * NB + activation row: the waves' partial sums in a fixed order, times the
+    // RMSNorm factor of its activation row
+    auto total = [&](int idx) {
+        float v = 0.f;
+        if constexpr (WAVES < 4) {
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) v += s_red[w][idx];
+        } else {
+#pragma unroll
+            for (int w = 0; w < WAVES; w += 4) v += (s_red[w][idx] + s_red[w + 1][idx]) + (s_red[w + 2][idx] + s_red[w + 3][idx]);
+        }
         if (norm) {
-            const int b = tid % NB;
-            const float ms = ((s_ssq[0][b] + s_ssq[1][b]) + (s_ssq[2][b] + s_ssq[3][b])) / static_cast<float>(a.K);
+            const int b = idx % NB;
+            float q = 0.f;
+            if constexpr (WAVES < 4) {
+#pragma unroll
+                for (int w = 0; w < WAVES; ++w) q += s_ssq[w][b];
+            } else {
+#pragma unroll
+                for (int w = 0; w < WAVES; w += 4) q += (s_ssq[w][b] + s_ssq[w + 1][b]) + (s_ssq[w + 2][b] + s_ssq[w + 3][b]);
+            }
+            const float ms = q / static_cast<float>(a.K);
             v *= 1.0f / sqrtf(ms + a.eps);
         }
-        s_val[tid] = v;
-    }
-    __syncthreads();
+        return v;
+    };
 
     if (a.epi == EPI_RESID || a.epi == EPI_STORE) {
         if (tid < R * NB) {
             const int r = tid / NB, b = tid % NB, n = row0 + r;
-            if (n < a.N && b < a.nb) {
-                const size_t i = static_cast<size_t>(b) * a.N + n;
-                a.out[i] = a.epi == EPI_RESID ? a.resid[i] + s_val[tid] : s_val[tid];
-            }
+            if (n < a.N && b < a.nb) a.out[static_cast<size_t>(b) * a.N + n] = pre_resid + total(tid);   // EPI_STORE: pre_resid is 0
         }
         return;
     }
@@ -149,7 +190,7 @@ __global__ __launch_bounds__(256) void decode_linear_kernel(DecodeLinear a, SeqB
     const int j = tid / NB, b = tid % NB;
     const int n0 = row0 + 2 * j;
     if (n0 >= a.N || b >= a.nb) return;
-    const float v0 = s_val[(2 * j) * NB + b], v1 = s_val[(2 * j + 1) * NB + b];
+    const float v0 = total((2 * j) * NB + b), v1 = total((2 * j + 1) * NB + b);
     if (a.epi == EPI_SWIGLU) {
         const int F = a.N / 2;
         a.out[static_cast<size_t>(b) * F + n0 / 2] = v0 / (1.0f + expf(-v0)) * v1;
@@ -157,38 +198,27 @@ __global__ __launch_bounds__(256) void decode_linear_kernel(DecodeLinear a, SeqB
     }
     // EPI_QKV
     const int dh = a.kv.dh, nq = a.hq * dh, nk = a.kv.hkv * dh;
-    const int pos = sb.pos[b];
     if (n0 < nq + nk) {  // q or k: rotate the pair
-        const int e = n0 % dh;
-        const float2 cs = a.rope[static_cast<size_t>(pos) * (dh / 2) + e / 2];
-        const float r0 = v0 * cs.x - v1 * cs.y, r1 = v0 * cs.y + v1 * cs.x;
+        const float r0 = v0 * pre_cs.x - v1 * pre_cs.y, r1 = v0 * pre_cs.y + v1 * pre_cs.x;
         if (n0 < nq) {
             a.q[static_cast<size_t>(b) * nq + n0] = r0;
             a.q[static_cast<size_t>(b) * nq + n0 + 1] = r1;
             return;
         }
-        const int hk = (n0 - nq) / dh;
-        const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
-        typedef typename ActOf<WT>::type CT;  // cache element type
         CT* kp = static_cast<CT*>(a.kv.k);
-        kp[at] = store_cast<CT>(r0, a.oflow);
-        kp[at + 1] = store_cast<CT>(r1, a.oflow);
+        kp[pre_at] = store_cast<CT>(r0, a.oflow);
+        kp[pre_at + 1] = store_cast<CT>(r1, a.oflow);
         return;
     }
-    {
-        typedef typename ActOf<WT>::type CT;
-        const int hk = (n0 - nq - nk) / dh, e = n0 % dh;
-        const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
-        CT* vp = static_cast<CT*>(a.kv.v);
-        vp[at] = store_cast<CT>(v0, a.oflow);
-        vp[at + 1] = store_cast<CT>(v1, a.oflow);
-    }
+    CT* vp = static_cast<CT*>(a.kv.v);
+    vp[pre_at] = store_cast<CT>(v0, a.oflow);
+    vp[pre_at + 1] = store_cast<CT>(v1, a.oflow);
 }
 
-template <typename WT, int NB, int R, int U, bool ROT = false>
+template <typename WT, int NB, int R, int U, bool ROT = false, int THREADS = 256>
 static void launch_dl(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
     const int grid = (a.N + R - 1) / R;
-    launch((decode_linear_kernel<WT, NB, R, U, ROT>), dim3(grid), dim3(256), 0, st, a, sb);
+    launch((decode_linear_kernel<WT, NB, R, U, ROT, THREADS>), dim3(grid), dim3(THREADS), 0, st, a, sb);
 }
 
 // (rows per workgroup, chunks in flight) from a sweep on MI355X over the Llama2 shapes:
@@ -197,9 +227,9 @@ static void launch_dl(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st)
 // (choose_decode_linear), so that tests can ask which variant a shape lands on.
 enum DlId { DL_NB1_WIDE, DL_NB1_LONGK, DL_NB1_SQUARE, DL_NB2, DL_NB4, DL_NB8, DL_ID_COUNT };
 static const char* const DL_NAMES[2][DL_ID_COUNT] = {
-    {"f32 stream nb1 r4 u1 (N >= 8192)", "f32 stream nb1 r4 u2 rot (K > 8192)", "f32 stream nb1 r2 u4", "f32 stream nb2 r4 u2",
+    {"f32 stream nb1 r4 u1 t512 (N >= 8192)", "f32 stream nb1 r4 u2 rot (K > 8192)", "f32 stream nb1 r2 u4", "f32 stream nb2 r4 u2",
      "f32 stream nb4 r4 u2", "f32 stream nb8 r4 u1"},
-    {"f16 stream nb1 r8 u1 (N >= 8192)", "f16 stream nb1 r4 u2 rot (K > 8192)", "f16 stream nb1 r4 u1", "f16 stream nb2 r4 u2",
+    {"f16 stream nb1 r8 u1 t512 (N >= 8192)", "f16 stream nb1 r4 u1 t512 (K > 8192)", "f16 stream nb1 r4 u1 t512", "f16 stream nb2 r4 u2",
      "f16 stream nb4 r4 u2", "f16 stream nb8 r4 u1"}};
 const char* decode_linear_variant_name(int id) {
     return id >= 0 && id < 2 * DL_ID_COUNT ? DL_NAMES[id / DL_ID_COUNT][id % DL_ID_COUNT] : nullptr;
@@ -218,9 +248,11 @@ template <typename WT>
 static void launch_dl_t(const DecodeLinear& a, const SeqBatch& sb, hipStream_t st) {
     constexpr bool f32 = sizeof(WT) == 4;
     switch (choose_decode_linear(a.wt, a.nb, a.N, a.K) % DL_ID_COUNT) {
-        case DL_NB1_WIDE: if (f32) launch_dl<WT, 1, 4, 1>(a, sb, st); else launch_dl<WT, 1, 8, 1>(a, sb, st); break;
-        case DL_NB1_LONGK: launch_dl<WT, 1, 4, 2, true>(a, sb, st); break;
-        case DL_NB1_SQUARE: if (f32) launch_dl<WT, 1, 2, 4>(a, sb, st); else launch_dl<WT, 1, 4, 1>(a, sb, st); break;
+        // threads per workgroup from the same sweep: 512 for the wide matrices and for all
+        // half-precision ones - each worth 1-3 % over 256
+        case DL_NB1_WIDE: if (f32) launch_dl<WT, 1, 4, 1, false, 512>(a, sb, st); else launch_dl<WT, 1, 8, 1, false, 512>(a, sb, st); break;
+        case DL_NB1_LONGK: if (f32) launch_dl<WT, 1, 4, 2, true>(a, sb, st); else launch_dl<WT, 1, 4, 1, false, 512>(a, sb, st); break;
+        case DL_NB1_SQUARE: if (f32) launch_dl<WT, 1, 2, 4>(a, sb, st); else launch_dl<WT, 1, 4, 1, false, 512>(a, sb, st); break;
         case DL_NB2: launch_dl<WT, 2, 4, 2>(a, sb, st); break;
         case DL_NB4: launch_dl<WT, 4, 4, 2>(a, sb, st); break;
         default: launch_dl<WT, 8, 4, 1>(a, sb, st); break;
@@ -248,12 +280,60 @@ void launch_decode_linear(const DecodeLinear& a, const SeqBatch& sb, hipStream_t
 typedef _Float16 f16x8_d __attribute__((ext_vector_type(8)));
 typedef float f32x4_d __attribute__((ext_vector_type(4)));
 
-// Tail shared by the matrix-core projection kernels: the waves' partial accumulators (and sums
-// of squares) meet in LDS in fixed order, then the epilogue.  s_red [WAVES][16 TILES][16],
-// s_val [16 TILES][16] and s_ssq [WAVES][16] are LDS scratch of the caller.
+// What the epilogue of the matrix-core projection kernels reads from memory, fetched by each
+// thread for its own outputs BEFORE the weight stream starts (element id = tid + i * THREADS of
+// the workgroup's [rows][16] outputs, pair id likewise of its [row pairs][16]): the end of the
+// workgroup is then arithmetic and stores, not a chain of dependent loads that every workgroup
+// of the launch would sit in at the same time.
 template <int TILES, int WAVES>
-__device__ __forceinline__ void mfma_linear_finish(const DecodeLinear& a, const SeqBatch& sb, const f32x4_d (&acc)[TILES], float ssq,
-                                                   int row0, int row_end, float* s_red, float* s_val, float* s_ssq) {
+struct MfmaEpiloguePre {
+    static constexpr int ROWS = 16 * TILES, THREADS = 64 * WAVES;
+    static constexpr int NS = (ROWS * 16 + THREADS - 1) / THREADS;   // single outputs per thread
+    static constexpr int NP = (ROWS * 8 + THREADS - 1) / THREADS;    // output pairs per thread
+    float resid[NS];
+    float2 cs[NP];
+    size_t at[NP];
+};
+
+template <int TILES, int WAVES>
+__device__ __forceinline__ void mfma_epilogue_prefetch(const DecodeLinear& a, const SeqBatch& sb, int row0, int row_end,
+                                                       MfmaEpiloguePre<TILES, WAVES>& p) {
+    typedef MfmaEpiloguePre<TILES, WAVES> P;
+    const int tid = threadIdx.x;
+    if (a.epi == EPI_RESID) {
+#pragma unroll
+        for (int i = 0; i < P::NS; ++i) {
+            const int id = tid + i * P::THREADS, r = id >> 4, b = id & 15, n = row0 + r;
+            p.resid[i] = (id < P::ROWS * 16 && n < row_end && b < a.nb) ? a.resid[static_cast<size_t>(b) * a.N + n] : 0.f;
+        }
+    } else if (a.epi == EPI_QKV) {
+        const int dh = a.kv.dh, nq = a.hq * dh, nk = a.kv.hkv * dh;
+#pragma unroll
+        for (int i = 0; i < P::NP; ++i) {
+            const int id = tid + i * P::THREADS, j = id >> 4, b = id & 15, n0 = row0 + 2 * j;
+            p.cs[i] = make_float2(1.f, 0.f);
+            p.at[i] = 0;
+            if (id < P::ROWS * 8 && n0 < row_end && b < a.nb) {
+                const int pos = sb.pos[b], e = n0 % dh;
+                if (n0 < nq + nk) p.cs[i] = a.rope[static_cast<size_t>(pos) * (dh / 2) + e / 2];
+                if (n0 >= nq) {
+                    const int hk = (n0 - nq - (n0 < nq + nk ? 0 : nk)) / dh;
+                    p.at[i] = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
+                }
+            }
+        }
+    }
+}
+
+// Tail shared by the matrix-core projection kernels: the waves' partial accumulators (and sums
+// of squares) meet in LDS, every output is summed over the waves in fixed order by the thread
+// that stores it, then the epilogue.  s_red [WAVES][16 TILES][16] and s_ssq [WAVES][16] are LDS
+// scratch of the caller.
+template <int TILES, int WAVES>
+__device__ __forceinline__ void mfma_linear_finish(const DecodeLinear& a, const f32x4_d (&acc)[TILES], float ssq,
+                                                   int row0, int row_end, float* s_red, float* s_ssq,
+                                                   const MfmaEpiloguePre<TILES, WAVES>& pre) {
+    typedef MfmaEpiloguePre<TILES, WAVES> P;
     constexpr int ROWS = 16 * TILES;
     constexpr int THREADS = 64 * WAVES;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -268,8 +348,7 @@ __device__ __forceinline__ void mfma_linear_finish(const DecodeLinear& a, const 
     ssq += __shfl_xor(ssq, 32, 64);
     if (g == 0) s_ssq[wave * 16 + l16] = ssq;
     __syncthreads();
-    for (int id = tid; id < ROWS * 16; id += THREADS) {
-        const int r = id >> 4, b = id & 15;
+    auto total = [&](int r, int b) {
         float v = 0.f;
 #pragma unroll
         for (int w = 0; w < WAVES; ++w) v += s_red[(w * ROWS + r) * 16 + b];
@@ -279,16 +358,16 @@ __device__ __forceinline__ void mfma_linear_finish(const DecodeLinear& a, const 
             for (int w = 0; w < WAVES; ++w) q += s_ssq[w * 16 + b];
             v *= 1.0f / sqrtf(q / static_cast<float>(K) + a.eps);
         }
-        s_val[r * 16 + b] = v;
-    }
-    __syncthreads();
+        return v;
+    };
 
     if (a.epi == EPI_RESID) {
-        for (int id = tid; id < ROWS * 16; id += THREADS) {
-            const int r = id >> 4, b = id & 15, n = row0 + r;
-            if (n < row_end && b < a.nb) {
+#pragma unroll
+        for (int i = 0; i < P::NS; ++i) {
+            const int id = tid + i * THREADS, r = id >> 4, b = id & 15, n = row0 + r;
+            if (id < ROWS * 16 && n < row_end && b < a.nb) {
                 const size_t at = static_cast<size_t>(b) * a.N + n;
-                const float y = a.resid[at] + s_val[r * 16 + b];
+                const float y = pre.resid[i] + total(r, b);
                 a.out[at] = y;
                 if (a.out_h) static_cast<f16_t*>(a.out_h)[at] = store_cast<f16_t>(y, a.oflow);
             }
@@ -296,39 +375,34 @@ __device__ __forceinline__ void mfma_linear_finish(const DecodeLinear& a, const 
         return;
     }
     // pair epilogues: one (row pair j, activation row b) per thread and trip
-    for (int id = tid; id < ROWS * 8; id += THREADS) {   // ROWS/2 row pairs x 16 activation rows
-        const int j = id >> 4, b = id & 15;
+    const int dh = a.kv.dh, nq = a.hq * dh, nk = a.kv.hkv * dh;
+#pragma unroll
+    for (int i = 0; i < P::NP; ++i) {   // ROWS/2 row pairs x 16 activation rows
+        const int id = tid + i * THREADS, j = id >> 4, b = id & 15;
         const int n0 = row0 + 2 * j;
-        if (n0 >= row_end || b >= a.nb) continue;
-        const float v0 = s_val[(2 * j) * 16 + b], v1 = s_val[(2 * j + 1) * 16 + b];
+        if (id >= ROWS * 8 || n0 >= row_end || b >= a.nb) continue;
+        const float v0 = total(2 * j, b), v1 = total(2 * j + 1, b);
         if (a.epi == EPI_SWIGLU) {
             const int F = a.N / 2;
             static_cast<f16_t*>(a.out_b)[static_cast<size_t>(b) * F + n0 / 2] = store_cast<f16_t>(v0 / (1.0f + expf(-v0)) * v1, a.oflow);
             continue;
         }
-        const int dh = a.kv.dh, nq = a.hq * dh, nk = a.kv.hkv * dh;
-        const int pos = sb.pos[b];
-        const int e = n0 % dh;
         if (n0 < nq + nk) {
-            const float2 cs = a.rope[static_cast<size_t>(pos) * (dh / 2) + e / 2];
+            const float2 cs = pre.cs[i];
             const float r0 = v0 * cs.x - v1 * cs.y, r1 = v0 * cs.y + v1 * cs.x;
             if (n0 < nq) {
                 a.q[static_cast<size_t>(b) * nq + n0] = r0;
                 a.q[static_cast<size_t>(b) * nq + n0 + 1] = r1;
                 continue;
             }
-            const int hk = (n0 - nq) / dh;
-            const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
             f16_t* kp = static_cast<f16_t*>(a.kv.k);
-            kp[at] = store_cast<f16_t>(r0, a.oflow);
-            kp[at + 1] = store_cast<f16_t>(r1, a.oflow);
+            kp[pre.at[i]] = store_cast<f16_t>(r0, a.oflow);
+            kp[pre.at[i] + 1] = store_cast<f16_t>(r1, a.oflow);
             continue;
         }
-        const int hk = (n0 - nq - nk) / dh;
-        const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
         f16_t* vp = static_cast<f16_t*>(a.kv.v);
-        vp[at] = store_cast<f16_t>(v0, a.oflow);
-        vp[at + 1] = store_cast<f16_t>(v1, a.oflow);
+        vp[pre.at[i]] = store_cast<f16_t>(v0, a.oflow);
+        vp[pre.at[i] + 1] = store_cast<f16_t>(v1, a.oflow);
     }
 }
 
@@ -355,6 +429,9 @@ __global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLi
     for (int t = 0; t < TILES; ++t)   // lanes past the workgroup's rows re-read its last row (a cache hit; never stored)
         wp[t] = W + static_cast<size_t>(min(row0 + t * 16 + l16, row_end - 1)) * K + g * 8;
     const f16_t* xp = X + static_cast<size_t>(l16 < a.nb ? l16 : 0) * K + g * 8;
+
+    MfmaEpiloguePre<TILES, WAVES> pre;
+    mfma_epilogue_prefetch<TILES, WAVES>(a, sb, row0, row_end, pre);
 
     f32x4_d acc[TILES];
 #pragma unroll
@@ -394,9 +471,8 @@ __global__ __launch_bounds__(64 * WAVES) void decode_linear_mfma_kernel(DecodeLi
     }
 
     __shared__ float s_red[WAVES * ROWS * 16];
-    __shared__ float s_val[ROWS * 16];
     __shared__ float s_ssq[WAVES * 16];
-    mfma_linear_finish<TILES, WAVES>(a, sb, acc, ssq, row0, row_end, s_red, s_val, s_ssq);
+    mfma_linear_finish<TILES, WAVES>(a, acc, ssq, row0, row_end, s_red, s_ssq, pre);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -461,6 +537,8 @@ __global__ __launch_bounds__(512) void decode_linear_dma_kernel(DecodeLinear a, 
 
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s) issue(s);
+    MfmaEpiloguePre<TILES, WAVES> pre;               // after the first stages are on their way
+    mfma_epilogue_prefetch<TILES, WAVES>(a, sb, row0, row_end, pre);
     for (int ks = 0; ks < ksteps; ++ks) {
         wait_vmcnt<NPER*(STAGES - 2)>();                 // this wave's loads of step ks have landed
         __syncthreads();                                 // ... everyone's; and stage (ks-1) % STAGES is free
@@ -488,9 +566,8 @@ __global__ __launch_bounds__(512) void decode_linear_dma_kernel(DecodeLinear a, 
     wait_vmcnt<0>();                                     // the reloads past the end
     __syncthreads();                                     // the ring is free: it becomes the reduction's scratch
     float* s_red = reinterpret_cast<float*>(smem_dl);
-    float* s_val = s_red + WAVES * ROWS * 16;
-    float* s_ssq = s_val + ROWS * 16;
-    mfma_linear_finish<TILES, WAVES>(a, sb, acc, ssq, row0, row_end, s_red, s_val, s_ssq);
+    float* s_ssq = s_red + WAVES * ROWS * 16;
+    mfma_linear_finish<TILES, WAVES>(a, acc, ssq, row0, row_end, s_red, s_ssq, pre);
 }
 
 template <int TILES, int STAGES>

@@ -109,6 +109,19 @@ __device__ __forceinline__ float group_sum(float v) {
     return v;
 }
 
+// Sum over the 64 lanes of a wave, the result in every lane, without the LDS crossbar: rows of 16
+// lanes by DPP (group_sum<16>), then the four row sums through scalar registers.  Used at the end
+// of the streaming projections, where a chain of six dependent cross-lane shuffles per value
+// was a visible part of every launch.
+__device__ __forceinline__ float wave_sum_rows(float v) {
+    v = group_sum<16>(v);
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
 // Direct global -> LDS load (global_load_lds_dwordx4, gfx950): lds_byte (wave-uniform) goes to M0
 // and lane l's 16 bytes land at lds_byte + 16 * l; no registers are occupied while the load is
 // in flight.  Inline assembly because the compiler, for its own direct-to-LDS builtin, waits for

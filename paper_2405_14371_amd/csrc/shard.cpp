@@ -314,9 +314,14 @@ void run_prefill(shard* s, shard::Work& wk, const SeqBatch& sb, int T, const flo
 // enough slices to put about three workgroups on every compute unit, but never slices
 // shorter than one trip of the kernel's token loop (longer slices cost little: the trips of
 // a slice are software-pipelined).
-int pick_nsplit(const shard* s, const SeqBatch& sb) {
+int max_context(const SeqBatch& sb) {   // the new token included
     int ctx = 1;
     for (int b = 0; b < sb.n; ++b) ctx = ctx > sb.pos[b] + 1 ? ctx : sb.pos[b] + 1;
+    return ctx;
+}
+
+int pick_nsplit(const shard* s, const SeqBatch& sb) {
+    const int ctx = max_context(sb);
     const int kdt = s->m.weight_dtype == SHARD_F32 ? DT_F32 : DT_F16;
     const int units = sb.n * s->m.n_heads / decode_attn_heads_per_group(kdt, s->m.head_dim, s->m.n_heads, s->m.n_kv_heads);
     if (ctx <= decode_attn_single_pass_ctx(kdt, s->m.head_dim, s->m.n_heads, s->m.n_kv_heads)) return 1;
