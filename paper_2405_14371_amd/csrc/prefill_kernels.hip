@@ -54,53 +54,129 @@ void launch_rmsnorm(const float* x, const float* gain, float eps, void* out, int
 // `val` = the four features n4..n4+3 (n4 % 4 == 0) of row m.
 // ---------------------------------------------------------------------------------------
 template <typename ET>
-__device__ __forceinline__ void gemm_epilogue(const PrefillGemm& a, const SeqBatch& sb, int m, int n4, const float val[4]) {
+__device__ __forceinline__ void gemm_epilogue(const PrefillGemm& a, int m, int n4, const float val[4]) {
     if (m >= a.M || n4 >= a.N) return;
     if (a.epi == EPI_PARTIAL) {
         float4 o; o.x = val[0]; o.y = val[1]; o.z = val[2]; o.w = val[3];
         *reinterpret_cast<float4*>(a.out + static_cast<size_t>(m) * a.N + n4) = o;
         return;
     }
+    // EPI_SWIGLU (the residual and the QKV epilogues are written out per tile below)
+    const int F = a.N / 2;
+    ET* op = static_cast<ET*>(a.out_act) + static_cast<size_t>(m) * F + n4 / 2;
+    op[0] = store_cast<ET>(val[0] / (1.0f + expf(-val[0])) * val[1], a.oflow);
+    op[1] = store_cast<ET>(val[2] / (1.0f + expf(-val[2])) * val[3], a.oflow);
+}
+
+// Epilogue of a wave's TN x TM accumulator tiles (tile (i, j): features n_base + 32 i .., rows
+// m_base + 32 j + l32; register v of a lane is feature 8 (v / 4) + 4 half + v % 4 of its tile).
+// The residual epilogue reads before it writes, and output and residual may be the same buffer,
+// so the compiler keeps every read behind the write before it: one memory round trip per 16
+// bytes, 32 of them in a row at the end of a 256 x 256 tile while the matrix cores idle (the
+// 70B-shape O projection ran 19 % below the gate/up projection for that reason alone).  Here
+// the four reads of a 32 x 32 tile go out together, and the next tile's reads before the
+// current tile's writes.
+template <typename ET, int TN, int TM>
+__device__ __forceinline__ void gemm_tile_epilogues(const PrefillGemm& a, const SeqBatch& sb, const f32x16 (&acc)[TN][TM],
+                                                    int n_base, int m_base, int l32, int half) {
     if (a.epi == EPI_RESID) {
-        const size_t i = static_cast<size_t>(m) * a.N + n4;
-        const float4 r = *reinterpret_cast<const float4*>(a.resid + i);
-        float4 o;
-        o.x = r.x + val[0]; o.y = r.y + val[1]; o.z = r.z + val[2]; o.w = r.w + val[3];
-        *reinterpret_cast<float4*>(a.out + i) = o;
-        return;
-    }
-    if (a.epi == EPI_SWIGLU) {
-        const int F = a.N / 2;
-        ET* op = static_cast<ET*>(a.out_act) + static_cast<size_t>(m) * F + n4 / 2;
-        op[0] = store_cast<ET>(val[0] / (1.0f + expf(-val[0])) * val[1], a.oflow);
-        op[1] = store_cast<ET>(val[2] / (1.0f + expf(-val[2])) * val[3], a.oflow);
-        return;
-    }
-    // EPI_QKV
-    const int dh = a.kv.dh, nq = a.hq * dh, nk = a.kv.hkv * dh;
-    const int b = m / a.T, t = m % a.T;
-    const int pos = sb.pos[b] + t;
-    float r[4] = {val[0], val[1], val[2], val[3]};
-    const int e = n4 % dh;
-    if (n4 < nq + nk) {
-        const float2* cs = a.rope + static_cast<size_t>(pos) * (dh / 2) + e / 2;
-        const float2 c0 = cs[0], c1 = cs[1];
-        r[0] = val[0] * c0.x - val[1] * c0.y;
-        r[1] = val[0] * c0.y + val[1] * c0.x;
-        r[2] = val[2] * c1.x - val[3] * c1.y;
-        r[3] = val[2] * c1.y + val[3] * c1.x;
-    }
-    if (n4 < nq) {
-        float4 o; o.x = r[0]; o.y = r[1]; o.z = r[2]; o.w = r[3];
-        *reinterpret_cast<float4*>(a.q + static_cast<size_t>(m) * nq + n4) = o;
-        return;
-    }
-    const bool is_k = n4 < nq + nk;
-    const int hk = (n4 - nq - (is_k ? 0 : nk)) / dh;
-    const size_t at = kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, hk) * dh + e;
-    ET* dst = static_cast<ET*>(is_k ? a.kv.k : a.kv.v) + at;
+        float4 r[2][4];
+        auto addr = [&](int t, int vq, bool* ok) {
+            const int i = t / TM, j = t % TM;
+            const int n4 = n_base + i * 32 + vq * 8 + half * 4, m = m_base + j * 32 + l32;
+            *ok = m < a.M && n4 < a.N;
+            return static_cast<size_t>(m) * a.N + n4;
+        };
+        auto fetch = [&](int t) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) dst[i] = store_cast<ET>(r[i], a.oflow);
+            for (int vq = 0; vq < 4; ++vq) {
+                bool ok;
+                const size_t at = addr(t, vq, &ok);
+                r[t & 1][vq] = ok ? *reinterpret_cast<const float4*>(a.resid + at) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        };
+        fetch(0);
+#pragma unroll
+        for (int t = 0; t < TN * TM; ++t) {
+            if (t + 1 < TN * TM) fetch(t + 1);
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                bool ok;
+                const size_t at = addr(t, vq, &ok);
+                if (!ok) continue;
+                const f32x16& c = acc[t / TM][t % TM];
+                const float4 x = r[t & 1][vq];
+                float4 o;
+                o.x = x.x + c[vq * 4]; o.y = x.y + c[vq * 4 + 1]; o.z = x.z + c[vq * 4 + 2]; o.w = x.w + c[vq * 4 + 3];
+                *reinterpret_cast<float4*>(a.out + at) = o;
+            }
+        }
+        return;
+    }
+    if (a.epi == EPI_QKV) {
+        // What depends on the ROW only - sequence, position, rotation-table row, cache row of the
+        // token's page - is worked out once per row tile (the block-table read included, and only
+        // if the wave's features reach into the K / V range), not once per 16 bytes of output; the
+        // four rotation-table reads of a 32 x 32 tile go out together.
+        const int dh = a.kv.dh, nq = a.hq * dh, nk = a.kv.hkv * dh;
+        const bool wave_has_kv = n_base + TN * 32 > nq;
+        const float2* rope_row[TM];
+        size_t cache_row[TM];   // row of (token, kv head 0) in units of dh elements; head hk adds hk * page
+        bool row_ok[TM];
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int m = m_base + j * 32 + l32;
+            row_ok[j] = m < a.M;
+            const int mm = row_ok[j] ? m : a.M - 1;
+            const int b = mm / a.T, pos = sb.pos[b] + (mm - b * a.T);
+            rope_row[j] = a.rope + static_cast<size_t>(pos) * (dh / 2);
+            cache_row[j] = wave_has_kv ? kv_row_div(a.kv, a.kv.block_table + static_cast<size_t>(sb.seq[b]) * a.kv.max_pages, pos, 0) : 0;
+        }
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j) {
+                const int m = m_base + j * 32 + l32;
+                float4 cs[4];   // (cos, sin) of the two pairs of each 16-byte group
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    const int n4 = n_base + i * 32 + vq * 8 + half * 4;
+                    cs[vq] = (n4 < nq + nk && n4 < a.N) ? *reinterpret_cast<const float4*>(rope_row[j] + (n4 % dh) / 2)
+                                                       : make_float4(1.f, 0.f, 1.f, 0.f);
+                }
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    const int n4 = n_base + i * 32 + vq * 8 + half * 4;
+                    if (!row_ok[j] || n4 >= a.N) continue;
+                    const f32x16& c = acc[i][j];
+                    const float v0 = c[vq * 4], v1 = c[vq * 4 + 1], v2 = c[vq * 4 + 2], v3 = c[vq * 4 + 3];
+                    const bool rot = n4 < nq + nk;   // v is not rotated
+                    const float r0 = rot ? v0 * cs[vq].x - v1 * cs[vq].y : v0, r1 = rot ? v0 * cs[vq].y + v1 * cs[vq].x : v1;
+                    const float r2 = rot ? v2 * cs[vq].z - v3 * cs[vq].w : v2, r3 = rot ? v2 * cs[vq].w + v3 * cs[vq].z : v3;
+                    if (n4 < nq) {
+                        *reinterpret_cast<float4*>(a.q + static_cast<size_t>(m) * nq + n4) = make_float4(r0, r1, r2, r3);
+                        continue;
+                    }
+                    const bool is_k = n4 < nq + nk;
+                    const int f = n4 - nq - (is_k ? 0 : nk), hk = f / dh, e = f - hk * dh;
+                    ET* dst = static_cast<ET*>(is_k ? a.kv.k : a.kv.v) + (cache_row[j] + static_cast<size_t>(hk) * a.kv.page) * dh + e;
+                    dst[0] = store_cast<ET>(r0, a.oflow); dst[1] = store_cast<ET>(r1, a.oflow);
+                    dst[2] = store_cast<ET>(r2, a.oflow); dst[3] = store_cast<ET>(r3, a.oflow);
+                }
+            }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const int n4 = n_base + i * 32 + vq * 8 + half * 4;
+                const int m = m_base + j * 32 + l32;
+                const float val[4] = {acc[i][j][vq * 4], acc[i][j][vq * 4 + 1], acc[i][j][vq * 4 + 2], acc[i][j][vq * 4 + 3]};
+                gemm_epilogue<ET>(a, m, n4, val);
+            }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -250,18 +326,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(PrefillGemm a, SeqBatch sb, i
         __syncthreads();
     }
 
-    // D[n][m]: register v of a lane is feature 8*(v/4) + 4*half + v%4, row l32 of its tile.
-#pragma unroll
-    for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < TM; ++j)
-#pragma unroll
-            for (int vq = 0; vq < 4; ++vq) {
-                const int n4 = n0 + wn * (BN / 2) + i * 32 + vq * 8 + half * 4;
-                const int m = m0 + wm * (BM / 2) + j * 32 + l32;
-                const float val[4] = {acc[i][j][vq * 4], acc[i][j][vq * 4 + 1], acc[i][j][vq * 4 + 2], acc[i][j][vq * 4 + 3]};
-                gemm_epilogue<AT>(a, sb, m, n4, val);
-            }
+    gemm_tile_epilogues<AT, TN, TM>(a, sb, acc, n0 + wn * (BN / 2), m0 + wm * (BM / 2), l32, half);
 }
 
 template <typename T, int BN, int BM, int ROWDW, int PITCH>
@@ -396,17 +461,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_dma_kernel(PrefillGemm a, S
     }
     wait_vmcnt<0>();                             // the reloads past the end
 
-#pragma unroll
-    for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < TM; ++j)
-#pragma unroll
-            for (int vq = 0; vq < 4; ++vq) {
-                const int n4 = n0 + wn * (BN / WN) + i * 32 + vq * 8 + half * 4;
-                const int m = m0 + wm * (BM / WM) + j * 32 + l32;
-                const float val[4] = {acc[i][j][vq * 4], acc[i][j][vq * 4 + 1], acc[i][j][vq * 4 + 2], acc[i][j][vq * 4 + 3]};
-                gemm_epilogue<AT>(ae, sb, m, n4, val);
-            }
+    gemm_tile_epilogues<AT, TN, TM>(ae, sb, acc, n0 + wn * (BN / WN), m0 + wm * (BM / WM), l32, half);
 }
 
 template <typename T, int BN, int BM, int ROWDW, int STAGES, int WN, int WM>
