@@ -302,7 +302,18 @@ def main():
                     help="comma-separated workloads measured after the main one with one timed step each and reported in "
                          "the line's `also` array; 'none' for none; default: the other BASELINE configurations when the "
                          "main workload is the default one")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="instead of a benchmark: copy a 1 GiB device tensor three times and exit - the known traffic "
+                         "against which the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled")
     args = ap.parse_args()
+    if args.calibrate_copy:
+        import torch
+        a = torch.ones(2 ** 28, device="cuda")          # 1 GiB of float32
+        for _ in range(3):
+            b = a.clone()                               # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 2 ** 30, "copy_bytes_written": 2 ** 30, "copies": 3, "checksum": float(b[12345])}))
+        return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs one shard on ONE GPU; --gpus > 1 is not supported "
               "(a shard is a single device's share of the pipeline)", file=sys.stderr)

@@ -812,6 +812,11 @@ __global__ __launch_bounds__(DH) void decode_attn_merge_kernel(DecodeAttn a) {
     const size_t pbase = static_cast<size_t>(bh) * a.nsplit;
     __shared__ float s_w[ATTN_MAX_SPLIT];
     __shared__ float s_L;
+    // the partial outputs do not depend on the slice weights: their loads go out first and are in
+    // flight while the weights are worked out (one memory round trip instead of two in a row)
+    float po[ATTN_MAX_SPLIT];
+#pragma unroll
+    for (int s = 0; s < ATTN_MAX_SPLIT; ++s) po[s] = s < a.nsplit ? a.part_o[(pbase + s) * DH + tid] : 0.f;
     if (tid < ATTN_MAX_SPLIT) {
         const bool have = tid < a.nsplit;
         const float ms = have ? a.part_ml[(pbase + tid) * 2] : -INFINITY;
@@ -827,9 +832,6 @@ __global__ __launch_bounds__(DH) void decode_attn_merge_kernel(DecodeAttn a) {
         if (tid == 0) s_L = lw;
     }
     __syncthreads();
-    float po[ATTN_MAX_SPLIT];
-#pragma unroll
-    for (int s = 0; s < ATTN_MAX_SPLIT; ++s) po[s] = s < a.nsplit ? a.part_o[(pbase + s) * DH + tid] : 0.f;
     float ox = 0.f;
 #pragma unroll
     for (int s = 0; s < ATTN_MAX_SPLIT; ++s) ox = fmaf(po[s], s_w[s], ox);
