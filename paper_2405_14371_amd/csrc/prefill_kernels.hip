@@ -527,14 +527,14 @@ static int pick_variant(const GemmVariant* v, int count, int M, int N) {
 enum GemmId {
     G32_DMA_128x128, G32_DMA_128x64, G32_DMA_192x64, G32_DMA_192x128, G32_DMA_128x64_K32, G32_DMA_128x64_SPLITK2,
     G32_REG_128x128, G32_REG_128x64,
-    G16_DMA_256x256, G16_DMA_256x128, G16_DMA_128x128, G16_DMA_128x64, G16_DMA_384x128, G16_DMA_64x64,
+    G16_DMA_256x256, G16_DMA_256x128, G16_DMA_128x128, G16_DMA_128x64, G16_DMA_384x128, G16_DMA_192x256, G16_DMA_64x64,
     G16_DMA_128x64_SPLITK, G16_REG_128x128_K32, G16_REG_128x128_K64, G16_REG_128x64,
     GEMM_ID_COUNT
 };
 static const char* const GEMM_NAMES[GEMM_ID_COUNT] = {
     "f32 dma 128x128", "f32 dma 128x64", "f32 dma 192x64", "f32 dma 192x128", "f32 dma 128x64 k32", "f32 dma 128x64 split-k 2",
     "f32 reg 128x128", "f32 reg 128x64",
-    "f16 dma 256x256", "f16 dma 256x128", "f16 dma 128x128", "f16 dma 128x64", "f16 dma 384x128", "f16 dma 64x64",
+    "f16 dma 256x256", "f16 dma 256x128", "f16 dma 128x128", "f16 dma 128x64", "f16 dma 384x128", "f16 dma 192x256", "f16 dma 64x64",
     "f16 dma 128x64 split-k", "f16 reg 128x128 k32", "f16 reg 128x128 k64", "f16 reg 128x64",
 };
 const char* prefill_gemm_variant_name(int id) { return id >= 0 && id < GEMM_ID_COUNT ? GEMM_NAMES[id] : nullptr; }
@@ -568,7 +568,10 @@ int choose_prefill_gemm(int dt, int M, int N, int K, int epi, bool has_part, siz
                                         {256, 128, 1, {1250.f, 0.f, 0.f}},
                                         {128, 128, 1, {1000.f, 0.f, 0.f}},
                                         {128, 64, 2, {650.f, 900.f, 0.f}},
-                                        {384, 128, 1, {1300.f, 0.f, 0.f}},   // 256 tiles for 12288 x 1024
+                                        {384, 128, 1, {1300.f, 0.f, 0.f}},
+                                        // 256 tiles for 12288 x 1024 and 460 for 22016 x 1024 (7B shapes at 1024 rows: 120 and
+                                        // 203 us against 126 and 223 us with 384 x 128), 216 for 5120 x 2048
+                                        {192, 256, 1, {1380.f, 0.f, 0.f}},
                                         {64, 64, 1, {330.f, 0.f, 0.f}}};     // a few dozen rows: more workgroups stream the weights
         // A projection back to d_model at small M has too few output tiles for the chip even with
         // the smallest tile (13B shape, M = 256: 160 tiles): K is split over 3 or 4 workgroup rows,
@@ -583,8 +586,8 @@ int choose_prefill_gemm(int dt, int M, int N, int K, int epi, bool has_part, siz
                 return G16_DMA_128x64_SPLITK;
             }
         }
-        static const int ids[] = {G16_DMA_256x256, G16_DMA_256x128, G16_DMA_128x128, G16_DMA_128x64, G16_DMA_384x128, G16_DMA_64x64};
-        return ids[pick_variant(v, 6, M, N)];
+        static const int ids[] = {G16_DMA_256x256, G16_DMA_256x128, G16_DMA_128x128, G16_DMA_128x64, G16_DMA_384x128, G16_DMA_192x256, G16_DMA_64x64};
+        return ids[pick_variant(v, 7, M, N)];
     }
     static const GemmVariant v[] = {{128, 128, 3, {390.f, 650.f, 850.f}},
                                     {128, 128, 2, {470.f, 800.f, 0.f}},
@@ -612,6 +615,7 @@ void launch_prefill_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t s
         case G16_DMA_128x128: launch_gemm_dma<f16_t, 128, 128, 32, 3, 2, 2>(as, sb, st); break;
         case G16_DMA_128x64: launch_gemm_dma<f16_t, 128, 64, 32, 3, 2, 2>(as, sb, st); break;
         case G16_DMA_384x128: launch_gemm_dma<f16_t, 384, 128, 32, 2, 4, 2>(as, sb, st); break;
+        case G16_DMA_192x256: launch_gemm_dma<f16_t, 192, 256, 32, 2, 2, 4>(as, sb, st); break;
         case G16_DMA_64x64: launch_gemm_dma<f16_t, 64, 64, 32, 6, 2, 2>(as, sb, st); break;
         case G16_DMA_128x64_SPLITK: launch_gemm_dma<f16_t, 128, 64, 32, 3, 2, 2>(as, sb, st); break;
         case G16_REG_128x128_K32: launch_gemm<f16_t, 128, 128, 16, 16>(as, sb, st); break;

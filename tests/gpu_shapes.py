@@ -100,9 +100,11 @@ CASES += [
     Case("7b-width-f32", "full 7B layer shapes, a ragged row count, streaming decode", synth.model_cfg("7b"), "f32", 1, (72,), 4, seed=1),
     Case("7b-width-bf16", "the same in bf16", synth.model_cfg("7b"), "bf16", 1, (72,), 4, seed=1),
     # tile variants of the half GEMM that only large M x N reach; the inner dimension is kept short
-    Case("bf16-prefill-256x256-tiles", "1024 tokens x (12288 QKV, 22016 gate/up) rows: the largest half tiles",
+    Case("bf16-prefill-192x256-tiles", "1024 tokens x (12288 QKV, 22016 gate/up) rows: 256 and 460 tiles of 192 x 256",
          tiny(d_model=128, n_heads=32, n_kv_heads=32, head_dim=128, ffn_dim=11008), "bf16", 1, (1024,), 1, n_layers=1, seed=91, gains=True),
-    Case("bf16-prefill-2048-rows", "2 x 1024 tokens against the same widths (row bands of 8 tiles and a second band)",
+    Case("bf16-prefill-384x128-tiles", "1152 tokens x 10240 QKV rows: 243 tiles of 384 x 128 (270 of 192 x 256 would need a second round)",
+         tiny(d_model=128, n_heads=64, n_kv_heads=8, head_dim=128, ffn_dim=1024), "bf16", 1, (1152,), 1, n_layers=1, seed=103, gains=True),
+    Case("bf16-prefill-2560-rows", "2 x 1280 tokens: the 256 x 256 tiles, row bands of 8 tiles and a second band",
          tiny(d_model=128, n_heads=16, n_kv_heads=16, head_dim=128, ffn_dim=5504), "bf16", 2, (1280,), 1, n_layers=1, seed=93, gains=True),
     Case("bf16-prefill-k-not-64", "inner dimensions 200 and 344: the register-staged half GEMM",
          tiny(d_model=200, n_heads=4, n_kv_heads=2, head_dim=64, ffn_dim=344), "bf16", 2, (150,), 2, seed=95, gains=True),
