@@ -528,14 +528,14 @@ enum GemmId {
     G32_DMA_128x128, G32_DMA_128x64, G32_DMA_192x64, G32_DMA_192x128, G32_DMA_128x64_K32, G32_DMA_128x64_SPLITK2,
     G32_REG_128x128, G32_REG_128x64,
     G16_DMA_256x256, G16_DMA_256x128, G16_DMA_128x128, G16_DMA_128x64, G16_DMA_384x128, G16_DMA_192x256, G16_DMA_64x64,
-    G16_DMA_128x64_SPLITK, G16_REG_128x128_K32, G16_REG_128x128_K64, G16_REG_128x64,
+    G16_DMA_128x64_SPLITK, G16_DMA_128x128_SPLITK, G16_REG_128x128_K32, G16_REG_128x128_K64, G16_REG_128x64,
     GEMM_ID_COUNT
 };
 static const char* const GEMM_NAMES[GEMM_ID_COUNT] = {
     "f32 dma 128x128", "f32 dma 128x64", "f32 dma 192x64", "f32 dma 192x128", "f32 dma 128x64 k32", "f32 dma 128x64 split-k 2",
     "f32 reg 128x128", "f32 reg 128x64",
     "f16 dma 256x256", "f16 dma 256x128", "f16 dma 128x128", "f16 dma 128x64", "f16 dma 384x128", "f16 dma 192x256", "f16 dma 64x64",
-    "f16 dma 128x64 split-k", "f16 reg 128x128 k32", "f16 reg 128x128 k64", "f16 reg 128x64",
+    "f16 dma 128x64 split-k", "f16 dma 128x128 split-k", "f16 reg 128x128 k32", "f16 reg 128x128 k64", "f16 reg 128x64",
 };
 const char* prefill_gemm_variant_name(int id) { return id >= 0 && id < GEMM_ID_COUNT ? GEMM_NAMES[id] : nullptr; }
 
@@ -573,16 +573,30 @@ int choose_prefill_gemm(int dt, int M, int N, int K, int epi, bool has_part, siz
                                         // 203 us against 126 and 223 us with 384 x 128), 216 for 5120 x 2048
                                         {192, 256, 1, {1380.f, 0.f, 0.f}},
                                         {64, 64, 1, {330.f, 0.f, 0.f}}};     // a few dozen rows: more workgroups stream the weights
-        // A projection back to d_model at small M has too few output tiles for the chip even with
-        // the smallest tile (13B shape, M = 256: 160 tiles): K is split over 3 or 4 workgroup rows,
-        // about two workgroups per compute unit in all, each at least 8 k-steps (measured alone:
-        // O 40 -> 35 us, down 102 -> 76 us; two slices gain nothing over the unsplit launch).
-        if (epi == EPI_RESID && has_part) {
-            long S = 512 / t64;
-            if (S > 4) S = 4;
-            if (S > K / 64 / 8) S = K / 64 / 8;
-            if (S >= 3 && elems % 4 == 0 && elems * S <= part_cap) {
-                *kslices = static_cast<int>(S);
+        // A projection back to d_model at small M has too few output tiles for the chip (13B shape,
+        // M = 256: 80 tiles of 128 x 128): K is split over S <= 4 rows of workgroups so that tiles x S
+        // comes out at one workgroup per compute unit or just below, each slice at least 8 k-steps, and
+        // splitk_reduce_kernel adds the slices.  Of the 128 x 128 and the 128 x 64 tile the one that
+        // puts more workgroups on the chip that way is taken, the larger on a tie (13B at M = 256,
+        // S = 3: O 36 -> 31 us, down 76 -> 60 us against 128 x 64 tiles with the same S; 7B down at
+        // M = 256 / 384 / 512: 51 -> 43, 84 -> 64, 84 -> 71 us; 13B at M = 128: 128 x 64 with S = 3,
+        // 23 us against 30 us with S = 4); from 256 tiles on nothing is split.
+        if (epi == EPI_RESID && has_part && elems % 4 == 0) {
+            const long t128 = static_cast<long>((M + 127) / 128) * ((N + 127) / 128);
+            auto slices = [&](long tiles) {
+                long S = 256 / tiles;
+                if (S > 4) S = 4;
+                if (S > K / 64 / 8) S = K / 64 / 8;
+                while (S >= 2 && elems * static_cast<size_t>(S) > part_cap) --S;
+                return S;
+            };
+            const long s128 = M > 64 ? slices(t128) : 0, s64 = slices(t64);
+            if (s128 >= 2 && t128 * s128 >= t64 * s64) {
+                *kslices = static_cast<int>(s128);
+                return G16_DMA_128x128_SPLITK;
+            }
+            if (s64 >= 2) {
+                *kslices = static_cast<int>(s64);
                 return G16_DMA_128x64_SPLITK;
             }
         }
@@ -618,6 +632,7 @@ void launch_prefill_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t s
         case G16_DMA_192x256: launch_gemm_dma<f16_t, 192, 256, 32, 2, 2, 4>(as, sb, st); break;
         case G16_DMA_64x64: launch_gemm_dma<f16_t, 64, 64, 32, 6, 2, 2>(as, sb, st); break;
         case G16_DMA_128x64_SPLITK: launch_gemm_dma<f16_t, 128, 64, 32, 3, 2, 2>(as, sb, st); break;
+        case G16_DMA_128x128_SPLITK: launch_gemm_dma<f16_t, 128, 128, 32, 3, 2, 2>(as, sb, st); break;
         case G16_REG_128x128_K32: launch_gemm<f16_t, 128, 128, 16, 16>(as, sb, st); break;
         case G16_REG_128x128_K64: launch_gemm<f16_t, 128, 128, 32, 32>(as, sb, st); break;
         default: launch_gemm<f16_t, 128, 64, 32, 32>(as, sb, st); break;

@@ -86,6 +86,8 @@ CASES += [Case(f"bf16-prefill-splitk-B{B}-T{T}", "K = 2048 in 4 slices; K = 2368
                tiny(d_model=256, n_heads=16, n_kv_heads=4, head_dim=128, ffn_dim=2368), "bf16", B, (T,), 2, seed=57, gains=True)
           for B, T in ((2, 37), (1, 200), (3, 128))]
 CASES += [
+    Case("bf16-prefill-splitk-128x128-tiles", "256 tokens x 4096 features back to d_model: 64 tiles of 128 x 128, K = 2048 and 2368 in 4 slices",
+         tiny(d_model=4096, n_heads=16, n_kv_heads=2, head_dim=128, ffn_dim=2368), "bf16", 1, (256,), 1, n_layers=1, seed=107, gains=True),
     Case("batch64-f32", "SHARD_MAX_BATCH sequences in one call, fp32: eight passes of 8 rows",
          tiny(d_model=512, n_heads=8, n_kv_heads=2, head_dim=64, ffn_dim=1024), "f32", 64, (3,), 2, n_layers=1, seed=73, gains=True),
     Case("batch64-bf16", "the same in bf16: four groups of 16 on the matrix cores",
