@@ -525,19 +525,56 @@ static int pick_variant(const GemmVariant* v, int count, int M, int N) {
 // Every variant the launchers below can take, by name: the selection (choose_prefill_gemm) is
 // a pure host function of the shape, so that tests can ask which variant a shape lands on.
 enum GemmId {
-    G32_DMA_128x128, G32_DMA_128x64, G32_DMA_192x64, G32_DMA_192x128, G32_DMA_128x64_K32, G32_DMA_128x64_SPLITK2,
+    G32_DMA_128x128, G32_DMA_128x64, G32_DMA_192x64, G32_DMA_192x128, G32_DMA_128x64_K32, G32_DMA_128x64_SPLITK, G32_DMA_128x128_SPLITK,
     G32_REG_128x128, G32_REG_128x64,
     G16_DMA_256x256, G16_DMA_256x128, G16_DMA_128x128, G16_DMA_128x64, G16_DMA_384x128, G16_DMA_192x256, G16_DMA_64x64,
     G16_DMA_128x64_SPLITK, G16_DMA_128x128_SPLITK, G16_REG_128x128_K32, G16_REG_128x128_K64, G16_REG_128x64,
     GEMM_ID_COUNT
 };
 static const char* const GEMM_NAMES[GEMM_ID_COUNT] = {
-    "f32 dma 128x128", "f32 dma 128x64", "f32 dma 192x64", "f32 dma 192x128", "f32 dma 128x64 k32", "f32 dma 128x64 split-k 2",
+    "f32 dma 128x128", "f32 dma 128x64", "f32 dma 192x64", "f32 dma 192x128", "f32 dma 128x64 k32", "f32 dma 128x64 split-k", "f32 dma 128x128 split-k",
     "f32 reg 128x128", "f32 reg 128x64",
     "f16 dma 256x256", "f16 dma 256x128", "f16 dma 128x128", "f16 dma 128x64", "f16 dma 384x128", "f16 dma 192x256", "f16 dma 64x64",
     "f16 dma 128x64 split-k", "f16 dma 128x128 split-k", "f16 reg 128x128 k32", "f16 reg 128x128 k64", "f16 reg 128x64",
 };
 const char* prefill_gemm_variant_name(int id) { return id >= 0 && id < GEMM_ID_COUNT ? GEMM_NAMES[id] : nullptr; }
+
+// Split K for a projection back to d_model with too few output tiles for the chip (13B shape,
+// M = 256: 80 tiles of 128 x 128): K goes over S <= 4 rows of workgroups (grid y) so that tiles x S
+// comes out at one workgroup per compute unit or just below, each slice at least 512 elements of
+// K, into an fp32 scratch, and splitk_reduce_kernel adds slices and residual in slice order.  Of
+// the 128 x 128 and the 128 x 64 tile the one that puts more workgroups on the chip that way is
+// taken, the larger on a tie.  Measured alone, half precision: 13B at M = 256, S = 3: O 36 -> 31 us,
+// down 76 -> 60 us against 128 x 64 tiles with the same S; 7B down at M = 256 / 384 / 512:
+// 51 -> 43, 84 -> 64, 84 -> 71 us; 13B at M = 128: 128 x 64 with S = 3, 23 us against 30 us with
+// S = 4.  fp32, 7B: M = 128 O 138 -> 45 us, down 363 -> 109 us (128 x 64, S = 4); M = 256 O 136 -> 78,
+// down 365 -> 189 us (128 x 128, S = 4); M = 512 (128 tiles of 128 x 128, S = 2) O 141, down 350 us
+// against 146 and 355 us with two slices over 128 x 64 tiles and 141 and 367 us unsplit.  From 256
+// tiles on a split loses.
+// Returns 0 (no split), 64 or 128 (the tile's row count) and the slice count.
+static int choose_split(int M, int N, int K, size_t part_cap, int* slices) {
+    const size_t elems = static_cast<size_t>(M) * N;
+    if (elems % 4 != 0) return 0;
+    const long t64 = static_cast<long>((M + 63) / 64) * ((N + 127) / 128);
+    const long t128 = static_cast<long>((M + 127) / 128) * ((N + 127) / 128);
+    auto fit = [&](long tiles) {
+        long S = 256 / tiles;
+        if (S > 4) S = 4;
+        if (S > K / 512) S = K / 512;
+        while (S >= 2 && elems * static_cast<size_t>(S) > part_cap) --S;
+        return S;
+    };
+    const long s128 = M > 64 ? fit(t128) : 0, s64 = fit(t64);
+    if (s128 >= 2 && t128 * s128 >= t64 * s64) {
+        *slices = static_cast<int>(s128);
+        return 128;
+    }
+    if (s64 >= 2) {
+        *slices = static_cast<int>(s64);
+        return 64;
+    }
+    return 0;
+}
 
 int choose_prefill_gemm(int dt, int M, int N, int K, int epi, bool has_part, size_t part_cap, int* kslices) {
     *kslices = 1;
@@ -550,12 +587,9 @@ int choose_prefill_gemm(int dt, int M, int N, int K, int epi, bool has_part, siz
                                             {192, 64, 2, {118.f, 138.f, 0.f}},   // 12288 x 512: two tiles per unit, both resident
                                             {192, 128, 2, {136.f, 144.f, 0.f}},  // 22016 x 512: 460 tiles, at most two per unit
                                             {128, 64, 2, {116.f, 131.f, 0.f}}};  // k-step 32
-            // at most one 128 x 64 tile per compute unit (projections back to d_model at M = 512): two
-            // K slices put two workgroups on every unit (alone: O 145 -> 136 us, down 364 -> 343 us
-            // with the reduction; three slices lose)
-            if (epi == EPI_RESID && has_part && t64 > 128 && t64 <= 256 && K >= 2048 && elems % 4 == 0 && elems * 2 <= part_cap) {
-                *kslices = 2;
-                return G32_DMA_128x64_SPLITK2;
+            if (epi == EPI_RESID && has_part) {   // too few output tiles for the chip: see choose_split
+                const int rows = choose_split(M, N, K, part_cap, kslices);
+                if (rows) return rows == 128 ? G32_DMA_128x128_SPLITK : G32_DMA_128x64_SPLITK;
             }
             static const int ids[] = {G32_DMA_128x128, G32_DMA_128x64, G32_DMA_192x64, G32_DMA_192x128, G32_DMA_128x64_K32};
             return ids[pick_variant(v, K % 32 == 0 ? 5 : 4, M, N)];
@@ -573,32 +607,9 @@ int choose_prefill_gemm(int dt, int M, int N, int K, int epi, bool has_part, siz
                                         // 203 us against 126 and 223 us with 384 x 128), 216 for 5120 x 2048
                                         {192, 256, 1, {1380.f, 0.f, 0.f}},
                                         {64, 64, 1, {330.f, 0.f, 0.f}}};     // a few dozen rows: more workgroups stream the weights
-        // A projection back to d_model at small M has too few output tiles for the chip (13B shape,
-        // M = 256: 80 tiles of 128 x 128): K is split over S <= 4 rows of workgroups so that tiles x S
-        // comes out at one workgroup per compute unit or just below, each slice at least 8 k-steps, and
-        // splitk_reduce_kernel adds the slices.  Of the 128 x 128 and the 128 x 64 tile the one that
-        // puts more workgroups on the chip that way is taken, the larger on a tie (13B at M = 256,
-        // S = 3: O 36 -> 31 us, down 76 -> 60 us against 128 x 64 tiles with the same S; 7B down at
-        // M = 256 / 384 / 512: 51 -> 43, 84 -> 64, 84 -> 71 us; 13B at M = 128: 128 x 64 with S = 3,
-        // 23 us against 30 us with S = 4); from 256 tiles on nothing is split.
-        if (epi == EPI_RESID && has_part && elems % 4 == 0) {
-            const long t128 = static_cast<long>((M + 127) / 128) * ((N + 127) / 128);
-            auto slices = [&](long tiles) {
-                long S = 256 / tiles;
-                if (S > 4) S = 4;
-                if (S > K / 64 / 8) S = K / 64 / 8;
-                while (S >= 2 && elems * static_cast<size_t>(S) > part_cap) --S;
-                return S;
-            };
-            const long s128 = M > 64 ? slices(t128) : 0, s64 = slices(t64);
-            if (s128 >= 2 && t128 * s128 >= t64 * s64) {
-                *kslices = static_cast<int>(s128);
-                return G16_DMA_128x128_SPLITK;
-            }
-            if (s64 >= 2) {
-                *kslices = static_cast<int>(s64);
-                return G16_DMA_128x64_SPLITK;
-            }
+        if (epi == EPI_RESID && has_part) {   // too few output tiles for the chip: see choose_split
+            const int rows = choose_split(M, N, K, part_cap, kslices);
+            if (rows) return rows == 128 ? G16_DMA_128x128_SPLITK : G16_DMA_128x64_SPLITK;
         }
         static const int ids[] = {G16_DMA_256x256, G16_DMA_256x128, G16_DMA_128x128, G16_DMA_128x64, G16_DMA_384x128, G16_DMA_192x256, G16_DMA_64x64};
         return ids[pick_variant(v, 7, M, N)];
@@ -621,7 +632,8 @@ void launch_prefill_gemm(const PrefillGemm& a, const SeqBatch& sb, hipStream_t s
         case G32_DMA_192x64: launch_gemm_dma<float, 192, 64, 16, 4, 2, 2>(as, sb, st); break;
         case G32_DMA_192x128: launch_gemm_dma<float, 192, 128, 16, 4, 2, 2>(as, sb, st); break;
         case G32_DMA_128x64_K32: launch_gemm_dma<float, 128, 64, 32, 3, 2, 2>(as, sb, st); break;
-        case G32_DMA_128x64_SPLITK2: launch_gemm_dma<float, 128, 64, 16, 4, 2, 2>(as, sb, st); break;
+        case G32_DMA_128x64_SPLITK: launch_gemm_dma<float, 128, 64, 16, 4, 2, 2>(as, sb, st); break;
+        case G32_DMA_128x128_SPLITK: launch_gemm_dma<float, 128, 128, 16, 4, 2, 2>(as, sb, st); break;
         case G32_REG_128x128: launch_gemm<float, 128, 128, 16, 16>(as, sb, st); break;
         case G32_REG_128x64: launch_gemm<float, 128, 64, 32, 32>(as, sb, st); break;
         case G16_DMA_256x256: launch_gemm_dma<f16_t, 256, 256, 32, 2, 4, 2>(as, sb, st); break;

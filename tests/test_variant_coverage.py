@@ -49,7 +49,7 @@ def test_every_variant_in_the_tables_is_reached_by_a_parity_case(lib):
 
 
 @pytest.mark.parametrize("name,proj,want", [
-    ("c2", "qkv", "f32 dma 192x64"), ("c2", "gateup", "f32 dma 192x128"), ("c2", "o", "f32 dma 128x64 split-k 2"),
+    ("c2", "qkv", "f32 dma 192x64"), ("c2", "gateup", "f32 dma 192x128"), ("c2", "o", "f32 dma 128x128 split-k"),
     ("c3", "qkv", "f16 dma 192x256"), ("c3", "gateup", "f16 dma 192x256"), ("c3", "down", "f16 dma 128x128"),
     ("c5", "gateup", "f16 dma 256x256"),
 ])
