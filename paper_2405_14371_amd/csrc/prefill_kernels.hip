@@ -9,18 +9,38 @@
 namespace shk {
 
 // ---------------------------------------------------------------------------------------
-// RMSNorm of rows: out = x * rsqrt(mean(x^2) + eps) * gain.  One workgroup per row.
+// RMSNorm of rows: out = x * rsqrt(mean(x^2) + eps) * gain.  One workgroup per row.  Rows of
+// up to 8192 elements (every Llama2 width) are held in registers: all loads of the row and of
+// the gains go out at once and the row is read once; wider rows take two passes.
 // ---------------------------------------------------------------------------------------
 template <typename OT>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
                                                       float eps, OT* __restrict__ out, int d) {
+    constexpr int NV = 8;   // float4 per thread in the register path
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* xr = x + static_cast<size_t>(blockIdx.x) * d;
     OT* orow = out + static_cast<size_t>(blockIdx.x) * d;
+    const bool in_regs = d <= 1024 * NV;
+    float4 v[NV], g[NV];
     float ssq = 0.f;
-    for (int c = tid * 4; c < d; c += 1024) {
-        const float4 t = *reinterpret_cast<const float4*>(xr + c);
-        ssq += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+    if (in_regs) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int c = tid * 4 + i * 1024;
+            v[i] = c < d ? *reinterpret_cast<const float4*>(xr + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int c = tid * 4 + i * 1024;
+            g[i] = c < d ? *reinterpret_cast<const float4*>(gain + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int i = 0; i < NV; ++i) ssq += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
+    } else {
+        for (int c = tid * 4; c < d; c += 1024) {
+            const float4 t = *reinterpret_cast<const float4*>(xr + c);
+            ssq += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+        }
     }
     __shared__ float s_part[4];
     ssq = wave_sum(ssq);
@@ -28,13 +48,21 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
     __syncthreads();
     const float tot = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
     const float r = 1.0f / sqrtf(tot / static_cast<float>(d) + eps);
-    for (int c = tid * 4; c < d; c += 1024) {
-        const float4 t = *reinterpret_cast<const float4*>(xr + c);
-        const float4 g = *reinterpret_cast<const float4*>(gain + c);
-        orow[c] = Elem<OT>::from_f32(t.x * r * g.x);
-        orow[c + 1] = Elem<OT>::from_f32(t.y * r * g.y);
-        orow[c + 2] = Elem<OT>::from_f32(t.z * r * g.z);
-        orow[c + 3] = Elem<OT>::from_f32(t.w * r * g.w);
+    auto put = [&](int c, const float4& t, const float4& gg) {
+        orow[c] = Elem<OT>::from_f32(t.x * r * gg.x);
+        orow[c + 1] = Elem<OT>::from_f32(t.y * r * gg.y);
+        orow[c + 2] = Elem<OT>::from_f32(t.z * r * gg.z);
+        orow[c + 3] = Elem<OT>::from_f32(t.w * r * gg.w);
+    };
+    if (in_regs) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int c = tid * 4 + i * 1024;
+            if (c < d) put(c, v[i], g[i]);
+        }
+    } else {
+        for (int c = tid * 4; c < d; c += 1024)
+            put(c, *reinterpret_cast<const float4*>(xr + c), *reinterpret_cast<const float4*>(gain + c));
     }
 }
 

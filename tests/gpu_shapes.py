@@ -98,6 +98,8 @@ CASES += [
          tiny(d_model=64, n_heads=32, n_kv_heads=32, head_dim=128, ffn_dim=11008), "f32", 1, (512,), 1, n_layers=1, seed=79, gains=True),
     Case("16500-tokens-page-1", "block-table row longer than the prefill attention's LDS copy; a decode slice over more "
          "pages than its LDS cache", tiny(), "f32", 1, (16500,), 2, n_layers=1, seed=71, page=1),
+    Case("d-model-8448-bf16", "rows wider than 8192 elements: the two-pass RMSNorm of the prefill",
+         tiny(d_model=8448, n_heads=2, n_kv_heads=1, head_dim=64, ffn_dim=128), "bf16", 2, (5,), 2, n_layers=1, seed=109, gains=True),
     Case("300-tokens", "many key tiles and context splits", tiny(), "f32", 1, (300,), 3, n_layers=1, seed=9),
     Case("7b-width-f32", "full 7B layer shapes, a ragged row count, streaming decode", synth.model_cfg("7b"), "f32", 1, (72,), 4, seed=1),
     Case("7b-width-bf16", "the same in bf16", synth.model_cfg("7b"), "bf16", 1, (72,), 4, seed=1),
